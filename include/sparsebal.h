@@ -1,0 +1,152 @@
+/*
+ * libsparsebal — packed (varlen), causal, GQA dynamic block-sparse attention, forward and
+ * backward, with a per-sequence sparsity budget.  MI355X (gfx950) only.
+ *
+ * The computation is the block-sparse attention of the SparseBalance paper (arXiv 2604.13847),
+ * section 2.2: keys/values are cut into fixed-size blocks, a routing score relates each query
+ * block to the mean of each key block (the MoBA indexer the paper reuses), the Top-K blocks are
+ * kept, and attention is one softmax over the kept keys (Eq. 2; Eq. 1 when every block is kept).
+ * The budget k (number of kept blocks) is set per sequence, which is what the paper's dynamic
+ * sparsity tuning (section 4.1, Algorithm 1 output) feeds into the kernel.
+ *
+ * Conventions
+ *   - Every function returns SB_OK (0) or a negative error; sb_last_error() gives thread-local text.
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses.
+ *   - The caller owns every buffer, including workspaces; the library never allocates or frees
+ *     device memory and never synchronises the stream.  All device work is enqueued on the
+ *     hipStream_t passed as `stream` (a null pointer is the default stream).  Host arrays are read
+ *     during the call only.
+ *   - Layouts are row-major and contiguous, last index fastest:
+ *       Q, O, dO, dQ : [T][Hq][D]     K, V, dK, dV : [T][Hkv][D]     LSE : [Hq][T] float
+ *     Block j of sequence s covers packed rows cu[s]+j*B .. min(cu[s]+(j+1)*B, cu[s+1])-1; blocks
+ *     are aligned to the sequence start and never straddle sequences.
+ *     n_s = ceil(L_s/B) blocks per sequence, NQB = sum_s n_s, qb_off[s] = sum_{t<s} n_t.
+ *   - Selection heads Hs: Hq in SB_SELECT_PER_QHEAD (one block list per query head) or Hkv in
+ *     SB_SELECT_PER_KVGROUP (one list shared by the Hq/Hkv query heads of a KV head; its score is
+ *     the sum of their scores).  Query head h reads KV head h / (Hq/Hkv).
+ *   - scores: per sequence a dense [Hs][n_s][n_s] float block at element offset Hs*sum_{t<s} n_t^2;
+ *     entry (hs,i,j) with j >= i is -infinity.
+ *   - Selection CSR: row id = hs*NQB + qb_off[s] + i has c(s,i) = min(k_s, i+1) entries, the block
+ *     indices (local to the sequence) kept by query block i, ascending, the last being i itself.
+ *     sel_rowptr is therefore a closed form of cu_seqlens and topk.
+ *   - Supported: block_size 64; head_dim 64 or 128; Hq % Hkv == 0; n_s <= SB_MAX_BLOCKS_PER_SEQ;
+ *     in SB_SELECT_PER_KVGROUP Hq/Hkv <= 8.  Anything else returns SB_ERR_UNSUPPORTED.
+ *   - Degenerate inputs: empty sequences are allowed; T == 0 or S == 0 is a no-op returning SB_OK;
+ *     k_s > n_s is clamped to n_s; k_s < 1 is an error.
+ */
+#ifndef SPARSEBAL_H
+#define SPARSEBAL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SB_OK 0
+#define SB_ERR_INVALID_ARG (-1)
+#define SB_ERR_UNSUPPORTED (-2)
+#define SB_ERR_WORKSPACE_TOO_SMALL (-3)
+#define SB_ERR_HIP (-4)
+
+#define SB_BF16 0 /* Q,K,V,O,dO,dQ,dK,dV are bfloat16 */
+#define SB_F32 1  /* they are float; the attention kernels round them to bfloat16 on entry */
+
+#define SB_SELECT_PER_QHEAD 0
+#define SB_SELECT_PER_KVGROUP 1
+
+#define SB_MAX_BLOCKS_PER_SEQ 16384
+
+typedef struct sb_problem {
+  int32_t total_tokens, num_seqs;          /* T, S */
+  int32_t num_q_heads, num_kv_heads;       /* Hq, Hkv */
+  int32_t head_dim, block_size;            /* D, B */
+  int32_t dtype;                           /* SB_BF16 | SB_F32 */
+  int32_t select_mode;                     /* SB_SELECT_PER_QHEAD | SB_SELECT_PER_KVGROUP */
+  float softmax_scale;                     /* the 1/sqrt(d) of Eq. 1-2; <= 0 means 1/sqrt(head_dim) */
+  float score_scale;                       /* factor on the routing score; <= 0 means softmax_scale */
+  const int32_t *cu_seqlens_host;          /* host [S+1], cu[0] = 0, non-decreasing, cu[S] = T */
+  const int32_t *cu_seqlens_dev;           /* dev  [S+1], same values */
+  const int32_t *topk_host;                /* host [S], budget k_s >= 1 counting the diagonal block */
+  const int32_t *topk_dev;                 /* dev  [S], same values */
+} sb_problem;
+
+/* Sizes a caller needs before allocating; filled on the host from sb_problem alone. */
+typedef struct sb_layout {
+  int64_t num_qblocks;   /* NQB */
+  int64_t sel_heads;     /* Hs */
+  int64_t scores_elems;  /* floats in `scores` */
+  int64_t pooled_elems;  /* floats in `kbar_out`: NQB*Hkv*D */
+  int64_t sel_rows;      /* Hs*NQB; sel_rowptr holds sel_rows+1 int32 */
+  int64_t sel_nnz;       /* int32 entries in sel_idx */
+  int64_t plan_bytes;    /* bytes of the `plan` buffer of sb_plan_worklist */
+  int64_t scores_ws_bytes, select_ws_bytes, fwd_ws_bytes, bwd_ws_bytes; /* bytes of the `ws` arguments */
+  int64_t attended_pairs_per_head_sum; /* sum over query heads of unmasked (query,key) pairs,
+                                          the diagonal block counted as its causal triangle */
+} sb_layout;
+
+/* Host only.  Validates the problem and fills `out`. */
+int sb_get_layout(const sb_problem *p, sb_layout *out);
+
+/* Host only.  Budget from a keep ratio: k_s = clamp(ceil(rho_s*n_s - 1e-6), 1, n_s), one budget per
+ * sequence (the budget is a count of selected blocks, paper section 2.2). */
+int sb_keep_ratio_to_topk(const int32_t *cu_seqlens_host, int32_t S, int32_t block_size,
+                          const float *keep_ratio_host, int32_t *topk_out_host);
+
+/* Host only.  Writes the closed-form CSR row pointers (sel_rows+1 int32) to a host array. */
+int sb_sel_rowptr_host(const sb_problem *p, int32_t *rowptr_out_host);
+
+/* Routing scores (paper section 2.2, MoBA indexer): score[s][hs][i][j] = score_scale *
+ * < mean of Q over query block i , mean of K over key block j > for j < i (summed over the group's
+ * query heads in SB_SELECT_PER_KVGROUP), -infinity for j >= i.  Means are over the valid tokens of a
+ * block.  q, k: dev, dtype per p->dtype.  kbar_out: dev [NQB][Hkv][D] float or null.  scores_out:
+ * dev, scores_elems floats.  ws: dev, scores_ws_bytes. */
+int sb_block_scores(const sb_problem *p, const void *q, const void *k, float *kbar_out, float *scores_out,
+                    void *ws, void *stream);
+
+/* Top-K block selection (paper section 2.2): for every row (s,hs,i) keep the diagonal block i plus
+ * the c(s,i)-1 best past blocks j < i under the total order (score descending, then block index
+ * ascending; -0 == +0; NaN below every number).  Bit-exact function of `scores`.  Writes
+ * sel_rowptr_out (dev, sel_rows+1 int32) and sel_idx_out (dev, sel_nnz int32).  ws: dev, select_ws_bytes. */
+int sb_select_topk(const sb_problem *p, const float *scores, int32_t *sel_rowptr_out, int32_t *sel_idx_out,
+                   void *ws, void *stream);
+
+/* Work plan for the attention kernels: query-major work items (s,hs,i) ordered by decreasing
+ * selected-block count (longest first, as in balanced partitioning by workload weight, paper
+ * section 4.3), the key-major transpose of the selection (for every (s,hs,j) the set of query
+ * blocks that kept j) and key-major items ordered by decreasing column weight.  plan_out: dev,
+ * plan_bytes, opaque; it is valid for this problem and this selection only. */
+int sb_plan_worklist(const sb_problem *p, const int32_t *sel_rowptr, const int32_t *sel_idx, void *plan_out,
+                     void *stream);
+
+/* Forward (Eq. 2): for every query row r of query block i and query head h,
+ * O_r = sum_j softmax_j(softmax_scale * q_r.k_j) v_j over the keys j of the selected blocks that are
+ * not in r's future; LSE_r = log sum_j exp(softmax_scale * q_r.k_j).  Any valid selection is
+ * accepted (ascending, unique, <= i, containing i).  o: dev like q; lse: dev [Hq][T] float;
+ * ws: dev, fwd_ws_bytes. */
+int sb_sparse_attn_fwd(const sb_problem *p, const void *q, const void *k, const void *v,
+                       const int32_t *sel_rowptr, const int32_t *sel_idx, const void *plan, void *o, float *lse,
+                       void *ws, void *stream);
+
+/* Backward of Eq. 2 with the selection held fixed: dQ, dK, dV from dO (dK, dV summed over the
+ * query heads of each KV head).  o and lse are the forward's outputs.  Deterministic: every output
+ * element is accumulated by one workgroup in a fixed order.  ws: dev, bwd_ws_bytes. */
+int sb_sparse_attn_bwd(const sb_problem *p, const void *q, const void *k, const void *v, const void *o,
+                       const float *lse, const void *d_o, const int32_t *sel_rowptr, const int32_t *sel_idx,
+                       const void *plan, void *dq, void *dk, void *dv, void *ws, void *stream);
+
+/* Instrumentation.  When enabled (flag != 0) the attention kernels add, for every workgroup, its
+ * run time in ticks of the 100 MHz constant clock to a per-compute-unit slot inside `ws`;
+ * sb_read_cu_busy copies the SB_CU_SLOTS slots of the last forward or backward call that used `ws`
+ * to host memory (it synchronises the stream). */
+#define SB_CU_SLOTS 512
+int sb_set_instrumentation(int flag);
+int sb_read_cu_busy(const void *ws, uint64_t *busy_out_host, void *stream);
+
+const char *sb_last_error(void);
+const char *sb_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARSEBAL_H */

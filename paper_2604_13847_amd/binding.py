@@ -1,0 +1,218 @@
+"""Thin ctypes binding of libsparsebal (include/sparsebal.h): argument marshalling only.
+
+Every step of the hot path runs inside the library's HIP kernels; torch is used here for device
+memory and the current stream.  There is no CPU fallback: if the shared library is missing the
+import of `lib()` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libsparsebal.so")
+
+SB_OK = 0
+SB_BF16, SB_F32 = 0, 1
+SB_SELECT_PER_QHEAD, SB_SELECT_PER_KVGROUP = 0, 1
+SB_CU_SLOTS = 512
+
+EXPORTS = ["sb_get_layout", "sb_keep_ratio_to_topk", "sb_sel_rowptr_host", "sb_block_scores", "sb_select_topk",
+           "sb_plan_worklist", "sb_sparse_attn_fwd", "sb_sparse_attn_bwd", "sb_set_instrumentation", "sb_read_cu_busy",
+           "sb_last_error", "sb_version"]
+
+
+class sb_problem(C.Structure):
+    _fields_ = [("total_tokens", C.c_int32), ("num_seqs", C.c_int32), ("num_q_heads", C.c_int32),
+                ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("block_size", C.c_int32), ("dtype", C.c_int32),
+                ("select_mode", C.c_int32), ("softmax_scale", C.c_float), ("score_scale", C.c_float),
+                ("cu_seqlens_host", C.c_void_p), ("cu_seqlens_dev", C.c_void_p), ("topk_host", C.c_void_p),
+                ("topk_dev", C.c_void_p)]
+
+
+class sb_layout(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("num_qblocks", "sel_heads", "scores_elems", "pooled_elems", "sel_rows", "sel_nnz",
+                                         "plan_bytes", "scores_ws_bytes", "select_ws_bytes", "fwd_ws_bytes", "bwd_ws_bytes",
+                                         "attended_pairs_per_head_sum")]
+
+
+_lib = None
+
+
+class SparseBalError(RuntimeError):
+    pass
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise SparseBalError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+        _lib = C.CDLL(LIB_PATH)
+        _lib.sb_last_error.restype = C.c_char_p
+        _lib.sb_version.restype = C.c_char_p
+    return _lib
+
+
+def _check(rc):
+    if rc != SB_OK:
+        raise SparseBalError(f"libsparsebal error {rc}: {lib().sb_last_error().decode()}")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, torch.Tensor):
+        assert t.is_contiguous()
+        return C.c_void_p(t.data_ptr())
+    return t.ctypes.data_as(C.c_void_p)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Problem:
+    """Holds sb_problem plus the host/device arrays it points to."""
+
+    def __init__(self, cu_seqlens, topk, Hq, Hkv, D, B=64, dtype=SB_BF16, select_mode=SB_SELECT_PER_QHEAD,
+                 softmax_scale=0.0, score_scale=0.0, device=None):
+        self.cu_host = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+        self.topk_host = np.ascontiguousarray(topk, dtype=np.int32)
+        self.S, self.T = len(self.cu_host) - 1, int(self.cu_host[-1]) if len(self.cu_host) else 0
+        self.device = device
+        if device is not None:
+            self.cu_dev = torch.from_numpy(self.cu_host).to(device)
+            self.topk_dev = torch.from_numpy(self.topk_host).to(device) if self.S else torch.zeros(1, dtype=torch.int32, device=device)
+        else:
+            self.cu_dev = self.topk_dev = None
+        self.c = sb_problem(self.T, self.S, Hq, Hkv, D, B, dtype, select_mode, softmax_scale, score_scale,
+                            self.cu_host.ctypes.data, self.cu_dev.data_ptr() if device is not None else None,
+                            self.topk_host.ctypes.data if self.S else None,
+                            self.topk_dev.data_ptr() if device is not None else None)
+        self.Hq, self.Hkv, self.D, self.B, self.dtype, self.select_mode = Hq, Hkv, D, B, dtype, select_mode
+        self.layout = sb_get_layout(self)
+
+    def ref(self):
+        return C.byref(self.c)
+
+
+def sb_get_layout(pb: Problem) -> sb_layout:
+    out = sb_layout()
+    _check(lib().sb_get_layout(pb.ref(), C.byref(out)))
+    return out
+
+
+def sb_keep_ratio_to_topk(cu_seqlens, block_size, keep_ratio) -> np.ndarray:
+    cu = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+    rho = np.ascontiguousarray(keep_ratio, dtype=np.float32)
+    out = np.zeros(len(rho), dtype=np.int32)
+    _check(lib().sb_keep_ratio_to_topk(_ptr(cu), len(rho), block_size, _ptr(rho), _ptr(out)))
+    return out
+
+
+def sb_sel_rowptr_host(pb: Problem) -> np.ndarray:
+    out = np.zeros(pb.layout.sel_rows + 1, dtype=np.int32)
+    _check(lib().sb_sel_rowptr_host(pb.ref(), _ptr(out)))
+    return out
+
+
+def _bytes(n, device):
+    return torch.empty(max(int(n), 256), dtype=torch.uint8, device=device)
+
+
+def sb_block_scores(pb: Problem, q, k, want_kbar=False, ws=None):
+    lay = pb.layout
+    scores = torch.empty(max(lay.scores_elems, 1), dtype=torch.float32, device=q.device)
+    kbar = torch.empty(max(lay.pooled_elems, 1), dtype=torch.float32, device=q.device) if want_kbar else None
+    ws = ws if ws is not None else _bytes(lay.scores_ws_bytes, q.device)
+    _check(lib().sb_block_scores(pb.ref(), _ptr(q), _ptr(k), _ptr(kbar), _ptr(scores), _ptr(ws), _stream()))
+    return (scores, kbar) if want_kbar else scores
+
+
+def sb_select_topk(pb: Problem, scores, ws=None):
+    lay = pb.layout
+    rowptr = torch.empty(lay.sel_rows + 1, dtype=torch.int32, device=scores.device)
+    idx = torch.empty(max(lay.sel_nnz, 1), dtype=torch.int32, device=scores.device)
+    ws = ws if ws is not None else _bytes(lay.select_ws_bytes, scores.device)
+    _check(lib().sb_select_topk(pb.ref(), _ptr(scores), _ptr(rowptr), _ptr(idx), _ptr(ws), _stream()))
+    return rowptr, idx
+
+
+def sb_plan_worklist(pb: Problem, sel_rowptr, sel_idx, plan=None):
+    plan = plan if plan is not None else _bytes(pb.layout.plan_bytes, sel_rowptr.device)
+    _check(lib().sb_plan_worklist(pb.ref(), _ptr(sel_rowptr), _ptr(sel_idx), _ptr(plan), _stream()))
+    return plan
+
+
+def sb_sparse_attn_fwd(pb: Problem, q, k, v, sel_rowptr, sel_idx, plan, o=None, lse=None, ws=None):
+    o = o if o is not None else torch.empty_like(q)
+    lse = lse if lse is not None else torch.empty((pb.Hq, pb.T), dtype=torch.float32, device=q.device)
+    ws = ws if ws is not None else _bytes(pb.layout.fwd_ws_bytes, q.device)
+    _check(lib().sb_sparse_attn_fwd(pb.ref(), _ptr(q), _ptr(k), _ptr(v), _ptr(sel_rowptr), _ptr(sel_idx), _ptr(plan),
+                                    _ptr(o), _ptr(lse), _ptr(ws), _stream()))
+    return o, lse
+
+
+def sb_sparse_attn_bwd(pb: Problem, q, k, v, o, lse, d_o, sel_rowptr, sel_idx, plan, dq=None, dk=None, dv=None, ws=None):
+    dq = dq if dq is not None else torch.empty_like(q)
+    dk = dk if dk is not None else torch.empty_like(k)
+    dv = dv if dv is not None else torch.empty_like(v)
+    ws = ws if ws is not None else _bytes(pb.layout.bwd_ws_bytes, q.device)
+    _check(lib().sb_sparse_attn_bwd(pb.ref(), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(sel_rowptr),
+                                    _ptr(sel_idx), _ptr(plan), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), _stream()))
+    return dq, dk, dv
+
+
+def sb_set_instrumentation(flag: bool):
+    _check(lib().sb_set_instrumentation(int(bool(flag))))
+
+
+def sb_read_cu_busy(ws) -> np.ndarray:
+    out = np.zeros(SB_CU_SLOTS, dtype=np.uint64)
+    _check(lib().sb_read_cu_busy(_ptr(ws), _ptr(out), _stream()))
+    return out
+
+
+def sb_version() -> str:
+    return lib().sb_version().decode()
+
+
+# ------------------------------------------------------------------ plan inspection (tests only)
+def plan_views(pb: Problem, plan: torch.Tensor):
+    """Decode the opaque plan for property tests; mirrors the layout order of the library."""
+    lay = pb.layout
+    S, NQB, Hs, Hkv = pb.S, lay.num_qblocks, lay.sel_heads, pb.Hkv
+
+    def up(x):
+        return (x + 255) // 256 * 256
+
+    o = 0
+    tab = {}
+    for name, size in (("qb_off", 4 * (S + 1)), ("sc_off", 8 * (S + 1)), ("row_base", 4 * (S + 1)), ("bm_off", 8 * (S + 1)),
+                       ("kclamp", 4 * (S + 1)), ("qb_seq", 4 * (NQB + 1))):
+        tab[name] = o
+        o = up(o + size)
+    tables_bytes = o
+    o = up(tables_bytes)
+    off = {}
+    for name, size in (("work_fwd", 4 * (Hs * NQB + 1)), ("colcost", 4 * (Hkv * NQB + 1)), ("work_bwd", 4 * (Hkv * NQB + 1)),
+                       ("bins", 4 * 4097)):
+        off[name] = o
+        o = up(o + size)
+    off["bitmap"] = o
+    raw = plan.cpu().numpy()
+
+    def view(start, count, dt):
+        return raw[start:start + count * np.dtype(dt).itemsize].view(dt)
+
+    return {
+        "qb_off": view(tab["qb_off"], S + 1, np.int32), "bm_off": view(tab["bm_off"], S + 1, np.int64),
+        "qb_seq": view(tab["qb_seq"], NQB, np.int32), "kclamp": view(tab["kclamp"], S, np.int32),
+        "work_fwd": view(off["work_fwd"], Hs * NQB, np.int32), "colcost": view(off["colcost"], Hkv * NQB, np.int32),
+        "work_bwd": view(off["work_bwd"], Hkv * NQB, np.int32),
+        "bitmap": raw[off["bitmap"]:].view(np.uint32),
+    }

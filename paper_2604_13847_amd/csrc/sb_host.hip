@@ -1,0 +1,283 @@
+// Host-side logic of libsparsebal: validation, closed-form sizes, device geometry tables.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "sb_internal.h"
+
+namespace sb {
+
+static thread_local char g_err[512] = "";
+int g_instrument = 0;
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+int make_geo(const sb_problem* p, Geo* g) {
+  if (!p || !g) { set_error("null problem"); return SB_ERR_INVALID_ARG; }
+  if (p->total_tokens < 0 || p->num_seqs < 0) { set_error("negative T or S"); return SB_ERR_INVALID_ARG; }
+  if (p->num_q_heads < 1 || p->num_kv_heads < 1 || p->num_q_heads % p->num_kv_heads != 0) {
+    set_error("num_q_heads (%d) must be a positive multiple of num_kv_heads (%d)", p->num_q_heads, p->num_kv_heads);
+    return SB_ERR_INVALID_ARG;
+  }
+  if (p->dtype != SB_BF16 && p->dtype != SB_F32) { set_error("dtype must be SB_BF16 or SB_F32"); return SB_ERR_INVALID_ARG; }
+  if (p->select_mode != SB_SELECT_PER_QHEAD && p->select_mode != SB_SELECT_PER_KVGROUP) {
+    set_error("bad select_mode %d", p->select_mode);
+    return SB_ERR_INVALID_ARG;
+  }
+  if (p->block_size != 64) { set_error("block_size %d unsupported (64 only)", p->block_size); return SB_ERR_UNSUPPORTED; }
+  if (p->head_dim != 64 && p->head_dim != 128) { set_error("head_dim %d unsupported (64 or 128)", p->head_dim); return SB_ERR_UNSUPPORTED; }
+  g->T = p->total_tokens; g->S = p->num_seqs; g->Hq = p->num_q_heads; g->Hkv = p->num_kv_heads;
+  g->G = g->Hq / g->Hkv; g->D = p->head_dim; g->B = p->block_size; g->mode = p->select_mode; g->dtype = p->dtype;
+  g->Hs = g->mode == SB_SELECT_PER_QHEAD ? g->Hq : g->Hkv;
+  if (g->mode == SB_SELECT_PER_KVGROUP && g->G > 8) {
+    set_error("SB_SELECT_PER_KVGROUP supports at most 8 query heads per KV head (got %d)", g->G);
+    return SB_ERR_UNSUPPORTED;
+  }
+  g->softmax_scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)g->D);
+  g->score_scale = p->score_scale > 0.f ? p->score_scale : g->softmax_scale;
+  g->NQB = 0; g->n_max = 0; g->scores_unit = 0; g->nnz_unit = 0; g->bm_words_unit = 0; g->pairs_unit = 0;
+  if (g->S == 0 || g->T == 0) {
+    if (g->S > 0 && p->cu_seqlens_host && p->cu_seqlens_host[g->S] != g->T) { set_error("cu_seqlens[S] != T"); return SB_ERR_INVALID_ARG; }
+    if (g->S == 0 && g->T != 0) { set_error("T != 0 with S == 0"); return SB_ERR_INVALID_ARG; }
+  }
+  if (g->S > 0) {
+    if (!p->cu_seqlens_host || !p->topk_host) { set_error("cu_seqlens_host and topk_host are required"); return SB_ERR_INVALID_ARG; }
+    const int32_t* cu = p->cu_seqlens_host;
+    if (cu[0] != 0 || cu[g->S] != g->T) { set_error("cu_seqlens must start at 0 and end at T"); return SB_ERR_INVALID_ARG; }
+    for (int s = 0; s < g->S; ++s) {
+      int64_t L = (int64_t)cu[s + 1] - cu[s];
+      if (L < 0) { set_error("cu_seqlens decreases at %d", s); return SB_ERR_INVALID_ARG; }
+      if (p->topk_host[s] < 1) { set_error("topk[%d] = %d < 1", s, p->topk_host[s]); return SB_ERR_INVALID_ARG; }
+      int64_t n = (L + g->B - 1) / g->B;
+      if (n > SB_MAX_BLOCKS_PER_SEQ) { set_error("sequence %d has %lld blocks > %d", s, (long long)n, SB_MAX_BLOCKS_PER_SEQ); return SB_ERR_UNSUPPORTED; }
+      int64_t k = p->topk_host[s] < n ? p->topk_host[s] : n;
+      g->NQB += n;
+      if (n > g->n_max) g->n_max = (int)n;
+      g->scores_unit += n * n;
+      g->nnz_unit += k * n - k * (k - 1) / 2;
+      g->bm_words_unit += n * ((n + 31) / 32);
+      // unmasked pairs: every past selected block is B x B except that the last query block may have
+      // fewer rows; the diagonal block contributes rows(rows+1)/2
+      for (int64_t i = 0; i < n; ++i) {
+        int64_t rows = (i + 1) * g->B <= L ? g->B : L - i * g->B;
+        int64_t c = k < i + 1 ? k : i + 1;
+        g->pairs_unit += (c - 1) * rows * g->B + rows * (rows + 1) / 2;
+      }
+    }
+  }
+  if ((int64_t)g->Hs * g->nnz_unit > 0x7fffffffLL || (int64_t)g->Hs * g->NQB + 1 > 0x7fffffffLL) {
+    set_error("selection too large for int32 row pointers");
+    return SB_ERR_UNSUPPORTED;
+  }
+  return SB_OK;
+}
+
+TableOffsets table_offsets(const Geo& g) {
+  TableOffsets t{};
+  size_t o = 0;
+  t.qb_off = o;   o = align_up(o + sizeof(int32_t) * (size_t)(g.S + 1));
+  t.sc_off = o;   o = align_up(o + sizeof(int64_t) * (size_t)(g.S + 1));
+  t.row_base = o; o = align_up(o + sizeof(int32_t) * (size_t)(g.S + 1));
+  t.bm_off = o;   o = align_up(o + sizeof(int64_t) * (size_t)(g.S + 1));
+  t.kclamp = o;   o = align_up(o + sizeof(int32_t) * (size_t)(g.S + 1));
+  t.qb_seq = o;   o = align_up(o + sizeof(int32_t) * (size_t)(g.NQB + 1));
+  t.bytes = o;
+  return t;
+}
+
+Tables make_tables(const Geo& g, const sb_problem* p, void* base) {
+  TableOffsets t = table_offsets(g);
+  char* b = (char*)base;
+  Tables r;
+  r.cu = p->cu_seqlens_dev;
+  r.qb_off = (const int32_t*)(b + t.qb_off);
+  r.sc_off = (const int64_t*)(b + t.sc_off);
+  r.row_base = (const int32_t*)(b + t.row_base);
+  r.bm_off = (const int64_t*)(b + t.bm_off);
+  r.kclamp = (const int32_t*)(b + t.kclamp);
+  r.qb_seq = (const int32_t*)(b + t.qb_seq);
+  return r;
+}
+
+PlanOffsets plan_offsets(const Geo& g) {
+  PlanOffsets p{};
+  size_t o = 0;
+  p.tables = o;   o = align_up(o + table_offsets(g).bytes);
+  p.work_fwd = o; o = align_up(o + sizeof(int32_t) * (size_t)(g.Hs * g.NQB + 1));
+  p.colcost = o;  o = align_up(o + sizeof(int32_t) * (size_t)(g.Hkv * g.NQB + 1));
+  p.work_bwd = o; o = align_up(o + sizeof(int32_t) * (size_t)(g.Hkv * g.NQB + 1));
+  p.bins = o;     o = align_up(o + sizeof(int32_t) * (size_t)(kBwdBins + 1));
+  p.bitmap = o;   o = align_up(o + sizeof(uint32_t) * (size_t)(g.Hs * g.bm_words_unit + 1));
+  p.bytes = o;
+  return p;
+}
+
+static WsOffsets ws_offsets(const Geo& g, bool bwd) {
+  WsOffsets w{};
+  size_t o = 0;
+  size_t qbytes = g.dtype == SB_F32 ? sizeof(uint16_t) * (size_t)g.T * g.Hq * g.D : 0;
+  size_t kbytes = g.dtype == SB_F32 ? sizeof(uint16_t) * (size_t)g.T * g.Hkv * g.D : 0;
+  w.cu_busy = o; o = align_up(o + sizeof(uint64_t) * SB_CU_SLOTS);
+  w.qc = o;  o = align_up(o + qbytes);
+  w.kc = o;  o = align_up(o + kbytes);
+  w.vc = o;  o = align_up(o + kbytes);
+  w.oc = o;  o = align_up(o + 0);
+  w.doc = o; o = align_up(o + (bwd ? qbytes : 0));
+  w.drow = o; o = align_up(o + (bwd ? sizeof(float) * (size_t)g.T * g.Hq : 0));
+  w.bytes = o;
+  return w;
+}
+WsOffsets fwd_ws_offsets(const Geo& g) { return ws_offsets(g, false); }
+WsOffsets bwd_ws_offsets(const Geo& g) { return ws_offsets(g, true); }
+
+size_t scores_ws_bytes(const Geo& g) {
+  // tables + pooled Q [NQB][Hq][D] float + pooled K [NQB][Hkv][D] float
+  return align_up(table_offsets(g).bytes) + align_up(sizeof(float) * (size_t)g.NQB * g.Hq * g.D) +
+         align_up(sizeof(float) * (size_t)g.NQB * g.Hkv * g.D);
+}
+
+// One workgroup: prefix sums over sequences, then the query-block -> sequence map.
+__global__ __launch_bounds__(1024) void geom_kernel(const int32_t* __restrict__ cu, const int32_t* __restrict__ topk, int S, int B,
+                                                    int64_t NQB, int32_t* qb_off, int64_t* sc_off, int32_t* row_base,
+                                                    int64_t* bm_off, int32_t* kclamp, int32_t* qb_seq) {
+  __shared__ long long sh[4][1024];
+  __shared__ long long carry[4];
+  const int tid = threadIdx.x;
+  if (tid < 4) carry[tid] = 0;
+  if (tid == 0) { qb_off[0] = 0; sc_off[0] = 0; row_base[0] = 0; bm_off[0] = 0; }
+  __syncthreads();
+  for (int base = 0; base < S; base += 1024) {
+    int s = base + tid;
+    long long v[4] = {0, 0, 0, 0};
+    if (s < S) {
+      long long L = cu[s + 1] - cu[s];
+      long long n = (L + B - 1) / B;
+      long long k = topk[s] < n ? topk[s] : n;
+      if (k < 1) k = n > 0 ? 1 : 0;
+      kclamp[s] = (int32_t)k;
+      v[0] = n; v[1] = n * n; v[2] = k * n - k * (k - 1) / 2; v[3] = n * ((n + 31) / 32);
+    }
+    for (int a = 0; a < 4; ++a) sh[a][tid] = v[a];
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {  // inclusive Hillis-Steele scan of the four columns
+      long long t[4];
+      for (int a = 0; a < 4; ++a) t[a] = tid >= off ? sh[a][tid - off] : 0;
+      __syncthreads();
+      for (int a = 0; a < 4; ++a) sh[a][tid] += t[a];
+      __syncthreads();
+    }
+    if (s < S) {
+      qb_off[s + 1] = (int32_t)(carry[0] + sh[0][tid]);
+      sc_off[s + 1] = carry[1] + sh[1][tid];
+      row_base[s + 1] = (int32_t)(carry[2] + sh[2][tid]);
+      bm_off[s + 1] = carry[3] + sh[3][tid];
+    }
+    __syncthreads();
+    if (tid < 4) carry[tid] += sh[tid][1023];
+    __syncthreads();
+  }
+  __threadfence_block();
+  __syncthreads();
+  // query block -> sequence by binary search over qb_off (written above by this workgroup)
+  for (long long qb = tid; qb < NQB; qb += 1024) {
+    int lo = 0, hi = S - 1;  // largest s with qb_off[s] <= qb and n_s > 0  (first s with qb_off[s+1] > qb)
+    while (lo < hi) {
+      int mid = (lo + hi) >> 1;
+      if (qb_off[mid + 1] > qb) hi = mid; else lo = mid + 1;
+    }
+    qb_seq[qb] = lo;
+  }
+}
+
+int launch_geom(const Geo& g, const sb_problem* p, void* base, hipStream_t st) {
+  if (g.S == 0) return SB_OK;
+  if (!p->cu_seqlens_dev || !p->topk_dev) { set_error("cu_seqlens_dev and topk_dev are required"); return SB_ERR_INVALID_ARG; }
+  TableOffsets t = table_offsets(g);
+  char* b = (char*)base;
+  hipLaunchKernelGGL(geom_kernel, dim3(1), dim3(1024), 0, st, p->cu_seqlens_dev, p->topk_dev, g.S, g.B, g.NQB,
+                     (int32_t*)(b + t.qb_off), (int64_t*)(b + t.sc_off), (int32_t*)(b + t.row_base),
+                     (int64_t*)(b + t.bm_off), (int32_t*)(b + t.kclamp), (int32_t*)(b + t.qb_seq));
+  SB_LAUNCH_CHECK("geom_kernel");
+  return SB_OK;
+}
+
+}  // namespace sb
+
+using namespace sb;
+
+extern "C" {
+
+const char* sb_last_error(void) { return g_err; }
+const char* sb_version(void) { return "libsparsebal 0.1 (gfx950)"; }
+
+int sb_get_layout(const sb_problem* p, sb_layout* out) {
+  if (!out) { set_error("null layout"); return SB_ERR_INVALID_ARG; }
+  Geo g;
+  int rc = make_geo(p, &g);
+  if (rc != SB_OK) return rc;
+  out->num_qblocks = g.NQB;
+  out->sel_heads = g.Hs;
+  out->scores_elems = (int64_t)g.Hs * g.scores_unit;
+  out->pooled_elems = g.NQB * g.Hkv * g.D;
+  out->sel_rows = (int64_t)g.Hs * g.NQB;
+  out->sel_nnz = (int64_t)g.Hs * g.nnz_unit;
+  out->plan_bytes = (int64_t)plan_offsets(g).bytes;
+  out->scores_ws_bytes = (int64_t)scores_ws_bytes(g);
+  out->select_ws_bytes = (int64_t)align_up(table_offsets(g).bytes);
+  out->fwd_ws_bytes = (int64_t)fwd_ws_offsets(g).bytes;
+  out->bwd_ws_bytes = (int64_t)bwd_ws_offsets(g).bytes;
+  out->attended_pairs_per_head_sum = g.pairs_unit * g.Hq;
+  return SB_OK;
+}
+
+int sb_keep_ratio_to_topk(const int32_t* cu, int32_t S, int32_t B, const float* rho, int32_t* out) {
+  if (S < 0 || B < 1 || (S > 0 && (!cu || !rho || !out))) { set_error("bad arguments"); return SB_ERR_INVALID_ARG; }
+  for (int s = 0; s < S; ++s) {
+    long long L = (long long)cu[s + 1] - cu[s];
+    if (L < 0) { set_error("cu_seqlens decreases at %d", s); return SB_ERR_INVALID_ARG; }
+    long long n = (L + B - 1) / B;
+    long long k = (long long)ceil((double)rho[s] * (double)n - 1e-6);
+    if (k > n) k = n;
+    if (k < 1) k = 1;
+    out[s] = (int32_t)k;
+  }
+  return SB_OK;
+}
+
+int sb_sel_rowptr_host(const sb_problem* p, int32_t* rowptr) {
+  Geo g;
+  int rc = make_geo(p, &g);
+  if (rc != SB_OK) return rc;
+  if (!rowptr) { set_error("null rowptr"); return SB_ERR_INVALID_ARG; }
+  int64_t pos = 0;
+  for (int hs = 0; hs < g.Hs; ++hs) {
+    int64_t qb = 0;
+    for (int s = 0; s < g.S; ++s) {
+      int64_t L = (int64_t)p->cu_seqlens_host[s + 1] - p->cu_seqlens_host[s];
+      int64_t n = (L + g.B - 1) / g.B, k = p->topk_host[s] < n ? p->topk_host[s] : n;
+      for (int64_t i = 0; i < n; ++i) {
+        rowptr[(int64_t)hs * g.NQB + qb + i] = (int32_t)pos;
+        pos += k < i + 1 ? k : i + 1;
+      }
+      qb += n;
+    }
+  }
+  rowptr[(int64_t)g.Hs * g.NQB] = (int32_t)pos;
+  return SB_OK;
+}
+
+int sb_set_instrumentation(int flag) { g_instrument = flag != 0; return SB_OK; }
+
+int sb_read_cu_busy(const void* ws, uint64_t* out, void* stream) {
+  if (!ws || !out) { set_error("null argument"); return SB_ERR_INVALID_ARG; }
+  SB_CHECK_HIP(hipMemcpyAsync(out, ws, sizeof(uint64_t) * SB_CU_SLOTS, hipMemcpyDeviceToHost, (hipStream_t)stream));
+  SB_CHECK_HIP(hipStreamSynchronize((hipStream_t)stream));
+  return SB_OK;
+}
+
+}  // extern "C"

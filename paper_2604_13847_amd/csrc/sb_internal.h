@@ -1,0 +1,106 @@
+// Internal declarations shared by the translation units of libsparsebal (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "sparsebal.h"
+
+namespace sb {
+
+typedef __bf16 bf16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+void set_error(const char* fmt, ...);
+
+#define SB_CHECK_HIP(expr)                                                         \
+  do {                                                                             \
+    hipError_t e_ = (expr);                                                        \
+    if (e_ != hipSuccess) {                                                        \
+      ::sb::set_error("%s failed: %s", #expr, hipGetErrorString(e_));              \
+      return SB_ERR_HIP;                                                           \
+    }                                                                              \
+  } while (0)
+
+#define SB_LAUNCH_CHECK(name)                                                      \
+  do {                                                                             \
+    hipError_t e_ = hipGetLastError();                                             \
+    if (e_ != hipSuccess) {                                                        \
+      ::sb::set_error("launch of %s failed: %s", name, hipGetErrorString(e_));     \
+      return SB_ERR_HIP;                                                           \
+    }                                                                              \
+  } while (0)
+
+// Host-side geometry derived from sb_problem in O(S).
+struct Geo {
+  int T = 0, S = 0, Hq = 0, Hkv = 0, G = 1, D = 0, B = 64, Hs = 0, mode = 0, dtype = 0;
+  float softmax_scale = 0.f, score_scale = 0.f;
+  int64_t NQB = 0;          // total query blocks
+  int n_max = 0;            // largest n_s
+  int64_t scores_unit = 0;  // sum n_s^2 (per selection head)
+  int64_t nnz_unit = 0;     // sum_s (k n - k(k-1)/2) (per selection head)
+  int64_t bm_words_unit = 0;  // sum_s n_s * ceil(n_s/32) (per selection head)
+  int64_t pairs_unit = 0;   // unmasked (query,key) pairs per query head
+};
+
+// Validates p and fills g; returns SB_OK or an error (message set).
+int make_geo(const sb_problem* p, Geo* g);
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// Device tables computed by geom_kernel from cu_seqlens_dev / topk_dev.
+struct TableOffsets {
+  size_t qb_off;     // int32 [S+1]   prefix of n_s
+  size_t sc_off;     // int64 [S+1]   prefix of n_s^2
+  size_t row_base;   // int32 [S+1]   prefix of c-sums (k n - k(k-1)/2)
+  size_t bm_off;     // int64 [S+1]   prefix of n_s*ceil(n_s/32)
+  size_t kclamp;     // int32 [S]     min(k_s, n_s)
+  size_t qb_seq;     // int32 [NQB]   sequence of each query block
+  size_t bytes;
+};
+TableOffsets table_offsets(const Geo& g);
+
+struct Tables {  // device pointers into a tables area
+  const int32_t* cu;
+  const int32_t* qb_off;
+  const int64_t* sc_off;
+  const int32_t* row_base;
+  const int64_t* bm_off;
+  const int32_t* kclamp;
+  const int32_t* qb_seq;
+};
+Tables make_tables(const Geo& g, const sb_problem* p, void* base);
+int launch_geom(const Geo& g, const sb_problem* p, void* base, hipStream_t st);
+
+// Layout of the opaque plan buffer.
+struct PlanOffsets {
+  size_t tables;     // TableOffsets area
+  size_t work_fwd;   // int32 [Hs*NQB]   row ids, longest first
+  size_t colcost;    // int32 [Hkv*NQB]  tiles in each key-major column (summed over the group's heads)
+  size_t work_bwd;   // int32 [Hkv*NQB]  column ids (g*NQB + qb), heaviest first
+  size_t bins;       // int32 [kBwdBins + 1] counting-sort cursors
+  size_t bitmap;     // uint32 [Hs * bm_words_unit] transpose bitmap: bit i of column (s,hs,j)
+  size_t bytes;
+};
+constexpr int kBwdBins = 4096;
+PlanOffsets plan_offsets(const Geo& g);
+
+struct WsOffsets {
+  size_t cu_busy;    // uint64 [SB_CU_SLOTS]
+  size_t qc, kc, vc, oc, doc;  // bf16 copies when dtype == SB_F32 (0 size otherwise)
+  size_t drow;       // float [Hq][T]
+  size_t bytes;
+};
+WsOffsets fwd_ws_offsets(const Geo& g);
+WsOffsets bwd_ws_offsets(const Geo& g);
+size_t scores_ws_bytes(const Geo& g);
+
+extern int g_instrument;
+
+}  // namespace sb

@@ -1,0 +1,139 @@
+// Work plan: longest-first ordering of the query-major items, the key-major transpose of the
+// selection as a bitmap, and heaviest-first ordering of the key-major columns.
+//
+// Query-major items.  Item (s,hs,i) costs c = min(k_s, i+1) selected tiles.  Because the cost is a
+// closed form of (k_s, n_s, i), the rank of an item in the order (cost descending, then sequence,
+// then query block, then head with the KV head fastest) is a closed form too: every thread
+// computes its own rank with one pass over the S sequences, without sorting or atomics.  Adjacent
+// ranks differ in the KV head first, so with workgroups dealt round-robin to the 8 XCDs each XCD's
+// L2 keeps seeing the same KV heads.
+//
+// Key-major transpose.  Bit i of word (s,hs,j,i/32) says query block i kept key block j.  Bits are
+// set with atomicOr, whose result does not depend on order, so the backward pass can walk a
+// column's query blocks in ascending order and accumulate deterministically.
+#include "sb_internal.h"
+
+namespace sb {
+
+__global__ __launch_bounds__(256) void plan_fwd_kernel(const int32_t* __restrict__ qb_off, const int32_t* __restrict__ kclamp,
+                                                       const int32_t* __restrict__ qb_seq, int S, int64_t NQB, int Hs,
+                                                       int Hkv, int G, int mode, int32_t* __restrict__ work_fwd) {
+  const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;  // row id = hs*NQB + qb
+  if (row >= (int64_t)Hs * NQB) return;
+  const int hs = (int)(row / NQB);
+  const int qb = (int)(row - (int64_t)hs * NQB);
+  const int s = qb_seq[qb];
+  const int i = qb - qb_off[s];
+  const int ks = kclamp[s];
+  const int c = min(ks, i + 1);
+  int64_t pos = 0;
+  for (int t = 0; t < S; ++t) {
+    const int nt = qb_off[t + 1] - qb_off[t], kt = kclamp[t];
+    if (nt == 0) continue;
+    if (kt > c) pos += (int64_t)Hs * (nt - c);                          // items of t with larger cost
+    if (t < s) pos += (int64_t)Hs * (kt == c ? nt - c + 1 : (kt > c ? 1 : 0));  // equal cost, earlier sequence
+  }
+  int hrank;  // order of the selection heads inside one query block: KV head fastest
+  if (mode == SB_SELECT_PER_QHEAD) hrank = (hs % G) * Hkv + hs / G; else hrank = hs;
+  pos += (c < ks) ? hrank : (int64_t)(i - (ks - 1)) * Hs + hrank;
+  work_fwd[pos] = (int32_t)row;
+}
+
+// one wavefront per CSR row: set the row's bit in each selected column and count the column weights
+__global__ __launch_bounds__(256) void plan_transpose_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ idx,
+                                                             const int32_t* __restrict__ qb_off, const int64_t* __restrict__ bm_off,
+                                                             const int32_t* __restrict__ qb_seq, int64_t NQB, int Hs, int G,
+                                                             int mode, uint32_t* __restrict__ bitmap, int32_t* __restrict__ colcost) {
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= (int64_t)Hs * NQB) return;
+  const int lane = threadIdx.x & 63;
+  const int hs = (int)(row / NQB);
+  const int qb = (int)(row - (int64_t)hs * NQB);
+  const int s = qb_seq[qb];
+  const int i = qb - qb_off[s];
+  const int n = qb_off[s + 1] - qb_off[s];
+  const int w = (n + 31) >> 5;
+  uint32_t* bm = bitmap + (int64_t)Hs * bm_off[s] + (int64_t)hs * n * w;
+  const int g = mode == SB_SELECT_PER_QHEAD ? hs / G : hs;
+  const int weight = mode == SB_SELECT_PER_QHEAD ? 1 : G;  // query-head tiles this entry stands for
+  for (int e = rowptr[row] + lane; e < rowptr[row + 1]; e += 64) {
+    const int j = idx[e];
+    atomicOr(&bm[(int64_t)j * w + (i >> 5)], 1u << (i & 31));
+    atomicAdd(&colcost[(int64_t)g * NQB + qb_off[s] + j], weight);
+  }
+}
+
+__global__ __launch_bounds__(256) void plan_bwd_hist_kernel(const int32_t* __restrict__ colcost, int64_t ncol, int32_t* __restrict__ bins) {
+  const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (c >= ncol) return;
+  atomicAdd(&bins[min(colcost[c], kBwdBins - 1)], 1);
+}
+
+// one workgroup: bins[b] <- number of columns with cost bin > b (start cursor of bin b in heaviest-first order)
+__global__ __launch_bounds__(1024) void plan_bwd_scan_kernel(int32_t* __restrict__ bins) {
+  __shared__ int sh[1024];
+  const int tid = threadIdx.x;
+  constexpr int per = kBwdBins / 1024;
+  int v[per], sum = 0;
+  // thread t owns bins (kBwdBins-1 - t*per) downwards
+#pragma unroll
+  for (int a = 0; a < per; ++a) { v[a] = bins[kBwdBins - 1 - (tid * per + a)]; sum += v[a]; }
+  sh[tid] = sum;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {
+    int t = tid >= off ? sh[tid - off] : 0;
+    __syncthreads();
+    sh[tid] += t;
+    __syncthreads();
+  }
+  int run = sh[tid] - sum;
+#pragma unroll
+  for (int a = 0; a < per; ++a) { bins[kBwdBins - 1 - (tid * per + a)] = run; run += v[a]; }
+}
+
+__global__ __launch_bounds__(256) void plan_bwd_scatter_kernel(const int32_t* __restrict__ colcost, int64_t ncol, int32_t* __restrict__ bins,
+                                                               int32_t* __restrict__ work_bwd) {
+  const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (c >= ncol) return;
+  const int pos = atomicAdd(&bins[min(colcost[c], kBwdBins - 1)], 1);
+  work_bwd[pos] = (int32_t)c;
+}
+
+}  // namespace sb
+
+using namespace sb;
+
+extern "C" int sb_plan_worklist(const sb_problem* p, const int32_t* sel_rowptr, const int32_t* sel_idx, void* plan_out,
+                                void* stream) {
+  Geo g;
+  int rc = make_geo(p, &g);
+  if (rc != SB_OK) return rc;
+  if (g.S == 0 || g.T == 0 || g.NQB == 0) return SB_OK;
+  if (!sel_rowptr || !sel_idx || !plan_out) { set_error("null sel_rowptr, sel_idx or plan_out"); return SB_ERR_INVALID_ARG; }
+  hipStream_t st = (hipStream_t)stream;
+  PlanOffsets po = plan_offsets(g);
+  char* base = (char*)plan_out;
+  rc = launch_geom(g, p, base + po.tables, st);
+  if (rc != SB_OK) return rc;
+  Tables t = make_tables(g, p, base + po.tables);
+  int32_t* work_fwd = (int32_t*)(base + po.work_fwd);
+  int32_t* colcost = (int32_t*)(base + po.colcost);
+  int32_t* work_bwd = (int32_t*)(base + po.work_bwd);
+  int32_t* bins = (int32_t*)(base + po.bins);
+  uint32_t* bitmap = (uint32_t*)(base + po.bitmap);
+  const int64_t rows = (int64_t)g.Hs * g.NQB, ncol = (int64_t)g.Hkv * g.NQB;
+  // colcost, work_bwd, bins and bitmap are adjacent: clear colcost, bins and bitmap
+  SB_CHECK_HIP(hipMemsetAsync(colcost, 0, po.bytes - po.colcost, st));
+  hipLaunchKernelGGL(plan_fwd_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, t.qb_off, t.kclamp, t.qb_seq,
+                     g.S, g.NQB, g.Hs, g.Hkv, g.G, g.mode, work_fwd);
+  SB_LAUNCH_CHECK("plan_fwd_kernel");
+  hipLaunchKernelGGL(plan_transpose_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, sel_rowptr, sel_idx, t.qb_off,
+                     t.bm_off, t.qb_seq, g.NQB, g.Hs, g.G, g.mode, bitmap, colcost);
+  SB_LAUNCH_CHECK("plan_transpose_kernel");
+  hipLaunchKernelGGL(plan_bwd_hist_kernel, dim3((unsigned)((ncol + 255) / 256)), dim3(256), 0, st, colcost, ncol, bins);
+  hipLaunchKernelGGL(plan_bwd_scan_kernel, dim3(1), dim3(1024), 0, st, bins);
+  hipLaunchKernelGGL(plan_bwd_scatter_kernel, dim3((unsigned)((ncol + 255) / 256)), dim3(256), 0, st, colcost, ncol, bins,
+                     work_bwd);
+  SB_LAUNCH_CHECK("plan_bwd kernels");
+  return SB_OK;
+}

@@ -1,0 +1,167 @@
+"""GPU parity: every call of the C-ABI library against the CPU checker on the same seeded inputs.
+
+Scores within float32 tolerance; selection bit-exact given identical scores; plan properties;
+O / LSE / dQ / dK / dV within max-abs 2e-2 and mean-abs 2e-3 of the float64 checker run on the same
+selection (the GPU's)."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import DEV, MAX_ABS, MEAN_ABS, Run, check_close, err_stats, to_host_f32
+from oracle import oracle as orc
+from paper_2604_13847_amd import binding as sb
+from paper_2604_13847_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def check_scores(r: Run):
+    got = r.scores.cpu().numpy()[: r.pb.layout.scores_elems]
+    q, k, _, _ = (r.host[n] for n in ("q", "k", "v", "do"))     # scores are computed from the stored values
+    ref = orc.block_scores(r.opb, q, k, r.scale)
+    assert np.array_equal(np.isneginf(got), np.isneginf(ref))
+    fin = np.isfinite(ref)
+    if fin.any():
+        scale = max(1e-3, float(np.abs(ref[fin]).max()))
+        assert np.abs(got[fin] - ref[fin]).max() <= 2e-5 * scale, np.abs(got[fin] - ref[fin]).max() / scale
+    return got
+
+
+def check_selection(r: Run, got_scores):
+    rp, idx = orc.select_topk(r.opb, got_scores, r.topk)       # decision on the GPU's own float32 scores
+    assert np.array_equal(r.rowptr_h, rp)
+    assert np.array_equal(r.idx_h, idx)
+
+
+def check_plan(r: Run):
+    pv = sb.plan_views(r.pb, r.plan)
+    lay, po = r.pb.layout, r.opb
+    NQB, Hs, Hkv, G = lay.num_qblocks, lay.sel_heads, r.w.Hkv, r.w.Hq // r.w.Hkv
+    assert np.array_equal(pv["qb_off"], po.qb_off.astype(np.int32))
+    wf = pv["work_fwd"]
+    assert np.array_equal(np.sort(wf), np.arange(Hs * NQB))                  # every item exactly once
+    cost = np.diff(r.rowptr_h)
+    assert np.all(np.diff(cost[wf]) <= 0)                                    # longest first
+    # bitmap is the exact transpose of the CSR
+    colcost = np.zeros(Hkv * NQB, dtype=np.int64)
+    bm = pv["bitmap"]
+    for s, n in enumerate(po.nblk):
+        w = (n + 31) // 32
+        for hs in range(Hs):
+            dense = np.zeros((n, n), dtype=bool)                             # dense[j, i]
+            for i in range(n):
+                row = hs * NQB + po.qb_off[s] + i
+                js = r.idx_h[r.rowptr_h[row]:r.rowptr_h[row + 1]]
+                dense[js, i] = True
+                g = hs // G if r.mode == 0 else hs
+                colcost[g * NQB + po.qb_off[s] + js] += 1 if r.mode == 0 else G
+            words = bm[Hs * pv["bm_off"][s] + hs * n * w: Hs * pv["bm_off"][s] + (hs + 1) * n * w].reshape(n, w)
+            bits = ((words[:, :, None] >> np.arange(32, dtype=np.uint32)) & 1).astype(bool).reshape(n, w * 32)[:, :n]
+            assert np.array_equal(bits, dense), (s, hs)
+    assert np.array_equal(pv["colcost"], colcost)
+    wb = pv["work_bwd"]
+    assert np.array_equal(np.sort(wb), np.arange(Hkv * NQB))
+    assert np.all(np.diff(np.minimum(colcost[wb], 4095)) <= 0)               # heaviest first
+    assert colcost.sum() == cost.sum() * (1 if r.mode == 0 else G)
+
+
+def check_attention(r: Run, bwd=True):
+    q, k, v, do = r.oracle_inputs()
+    O, LSE = orc.attn_fwd(r.opb, q, k, v, r.rowptr_h, r.idx_h, r.scale)
+    stats = {"O": check_close("O", to_host_f32(r.o), O)}
+    lse = r.lse.cpu().numpy()
+    assert np.abs(lse - LSE).max() <= 1e-2, np.abs(lse - LSE).max()
+    if bwd:
+        dQ, dK, dV = orc.attn_bwd(r.opb, q, k, v, do, r.rowptr_h, r.idx_h, r.scale)
+        stats["dQ"] = check_close("dQ", to_host_f32(r.dq), dQ)
+        stats["dK"] = check_close("dK", to_host_f32(r.dk), dK)
+        stats["dV"] = check_close("dV", to_host_f32(r.dv), dV)
+    return stats
+
+
+def full_check(w, mode, **kw):
+    r = Run(w, mode, **kw)
+    sc = check_scores(r)
+    check_selection(r, sc)
+    check_plan(r)
+    print(w, "mode", mode, check_attention(r), flush=True)
+    return r
+
+
+def test_config1_fp32_inputs():
+    for seed in (0, 1):
+        full_check(synth.config1(seed), sb.SB_SELECT_PER_QHEAD)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("D", [64, 128])
+def test_small_ragged_batches(mode, D):
+    # several tiles per sequence, ragged tails, a 1-token sequence, an empty sequence, a <1-block sequence
+    w = synth.small_ragged(seed=3, lens=(200, 64, 1, 130, 0, 77, 450), Hq=4, Hkv=2, D=D, ratio=(0.3, 0.9))
+    full_check(w, mode)
+
+
+@pytest.mark.parametrize("G", [1, 2, 3, 7, 8])
+def test_group_sizes_per_kvgroup(G):
+    w = synth.small_ragged(seed=4, lens=(300, 65), Hq=G, Hkv=1, D=128, ratio=(0.4, 0.8))
+    full_check(w, sb.SB_SELECT_PER_KVGROUP)
+    w = synth.small_ragged(seed=5, lens=(130, 190), Hq=2 * G, Hkv=2, D=64, ratio=(0.4, 0.8))
+    full_check(w, sb.SB_SELECT_PER_QHEAD)
+
+
+def test_full_budget_equals_dense_causal():
+    w = synth.small_ragged(seed=6, lens=(333, 100), Hq=4, Hkv=2, D=128, ratio=(1.0, 1.0))
+    r = full_check(w, 0)
+    assert np.array_equal(r.topk, r.opb.nblk)
+
+
+def test_budget_one_and_long_row():
+    w = synth.small_ragged(seed=7, lens=(64 * 40 + 5,), Hq=2, Hkv=1, D=64, ratio=(0.0, 0.0))     # k = 1
+    full_check(w, 0)
+    w = synth.small_ragged(seed=8, lens=(64 * 300 + 17,), Hq=2, Hkv=2, D=64, ratio=(0.05, 0.05))  # 301 blocks, k = 16
+    r = Run(w, 0, do_bwd=False)
+    check_selection(r, check_scores(r))
+    check_plan(r)
+
+
+def test_selection_ties_nan_and_zero_bit_exact():
+    # hand the selector adversarial scores: many exact ties, NaN, +-0, +-inf
+    w = synth.small_ragged(seed=9, lens=(64 * 70, 64 * 9 + 1), Hq=4, Hkv=2, D=64)
+    for mode in (0, 1):
+        topk = np.array([9, 3], dtype=np.int32)
+        pb = sb.Problem(w.cu, topk, w.Hq, w.Hkv, w.D, select_mode=mode, device=DEV)
+        po = orc.Problem(w.cu, w.Hq, w.Hkv, w.D, 64, mode)
+        rng = np.random.default_rng(3)
+        sc = rng.integers(-3, 4, size=pb.layout.scores_elems).astype(np.float32)
+        for val, p in ((np.nan, .05), (-np.inf, .05), (-0.0, .05), (0.0, .05), (np.inf, .03)):
+            sc[rng.random(sc.size) < p] = val
+        rowptr, idx = sb.sb_select_topk(pb, torch.from_numpy(sc).to(DEV))
+        rp, ix = orc.select_topk(po, sc, topk)
+        assert np.array_equal(rowptr.cpu().numpy(), rp)
+        assert np.array_equal(idx.cpu().numpy()[: rp[-1]], ix)
+
+
+def test_caller_supplied_selection_and_determinism():
+    # any valid selection is accepted: use the checker's selection from its own float64 scores
+    w = synth.small_ragged(seed=10, lens=(500, 129), Hq=4, Hkv=2, D=128, ratio=(0.3, 0.5))
+    topk = sb.sb_keep_ratio_to_topk(w.cu, 64, w.keep_ratio)
+    po = orc.Problem(w.cu, w.Hq, w.Hkv, w.D, 64, 0)
+    t = w.tensors()
+    sel = orc.select_topk(po, orc.block_scores(po, t["q"], t["k"], 1 / np.sqrt(128)).astype(np.float32), topk)
+    r1 = Run(w, 0, sel_override=sel)
+    check_attention(r1)
+    r2 = Run(w, 0, sel_override=sel)
+    for a, b in ((r1.o, r2.o), (r1.lse, r2.lse), (r1.dq, r2.dq), (r1.dk, r2.dk), (r1.dv, r2.dv)):
+        assert torch.equal(a, b)                       # run-to-run bitwise identical
+
+
+def test_empty_problem_is_a_noop():
+    pb = sb.Problem([0, 0], [1], 4, 2, 64, device=DEV)
+    z = torch.zeros(8, dtype=torch.bfloat16, device=DEV)
+    sc = sb.sb_block_scores(pb, z, z)
+    rowptr, idx = sb.sb_select_topk(pb, sc)
+    plan = sb.sb_plan_worklist(pb, rowptr, idx)
+    o, lse = sb.sb_sparse_attn_fwd(pb, z, z, z, rowptr, idx, plan)
+    sb.sb_sparse_attn_bwd(pb, z, z, z, o, lse, z, rowptr, idx, plan)
+    torch.cuda.synchronize()
+    assert rowptr.cpu().numpy()[0] == 0

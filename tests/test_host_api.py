@@ -1,0 +1,90 @@
+"""CPU-only tests of the C-ABI library: it loads, exports every declared symbol, and its host
+logic (validation, closed-form sizes, budget rule, row pointers) agrees with the CPU checker."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2604_13847_amd import binding as sb
+from paper_2604_13847_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "sparsebal.h")).read()
+    declared = set(re.findall(r"\b(sb_[a-z_0-9]+)\s*\(", hdr))
+    assert {"sb_block_scores", "sb_select_topk", "sb_plan_worklist", "sb_sparse_attn_fwd", "sb_sparse_attn_bwd"} <= declared
+    lib = sb.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert set(sb.EXPORTS) == declared
+    assert "gfx950" in sb.sb_version()
+
+
+@pytest.mark.parametrize("maker", [synth.config1, synth.config2, synth.config3, synth.config5, synth.small_ragged])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_layout_matches_checker_counts(maker, mode):
+    w = maker(1)
+    topk = w.topk if w.topk is not None else sb.sb_keep_ratio_to_topk(w.cu, w.B, w.keep_ratio)
+    if w.keep_ratio is not None:
+        assert np.array_equal(topk, orc.keep_ratio_to_topk(w.cu, w.B, w.keep_ratio))
+    pb = sb.Problem(w.cu, topk, w.Hq, w.Hkv, w.D, w.B, select_mode=mode)
+    po = orc.Problem(w.cu, w.Hq, w.Hkv, w.D, w.B, mode)
+    lay = pb.layout
+    assert lay.num_qblocks == po.NQB and lay.sel_heads == po.Hs
+    assert lay.scores_elems == int(po.score_off[-1])
+    rp = orc.sel_rowptr(po, topk)
+    assert np.array_equal(sb.sb_sel_rowptr_host(pb), rp) and lay.sel_nnz == rp[-1] and lay.sel_rows == len(rp) - 1
+    # unmasked pairs, counted straight from the definition
+    pairs = 0
+    for s, n in enumerate(po.nblk):
+        L = int(w.cu[s + 1] - w.cu[s])
+        k = min(int(topk[s]), n)
+        for i in range(n):
+            rows = min(w.B, L - i * w.B)
+            pairs += (min(k, i + 1) - 1) * rows * w.B + rows * (rows + 1) // 2
+    assert lay.attended_pairs_per_head_sum == pairs * w.Hq
+
+
+def test_keep_ratio_rule():
+    cu = np.array([0, 640, 705, 1705, 1708], dtype=np.int32)
+    assert sb.sb_keep_ratio_to_topk(cu, 64, [0.1, 0.5, 0.26, 0.9]).tolist() == [1, 1, 5, 1]
+    assert sb.sb_keep_ratio_to_topk(cu, 64, [0.0, 1.0, 2.0, 0.0]).tolist() == [1, 2, 16, 1]
+
+
+def _problem(**kw):
+    base = dict(cu_seqlens=[0, 100], topk=[2], Hq=4, Hkv=2, D=64)
+    base.update(kw)
+    return base
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(Hq=3), -1), (dict(D=96), -2), (dict(B=128), -2), (dict(topk=[0]), -1), (dict(cu_seqlens=[0, 50, 40]), -1),
+    (dict(cu_seqlens=[1, 100]), -1), (dict(dtype=7), -1), (dict(select_mode=3), -1),
+    (dict(Hq=18, Hkv=2, select_mode=1), -2), (dict(cu_seqlens=[0, 64 * 16385], topk=[1]), -2),
+])
+def test_invalid_problems_are_rejected(kw, code):
+    args = _problem(**kw)
+    if len(args["topk"]) != len(args["cu_seqlens"]) - 1:
+        args["topk"] = [1] * (len(args["cu_seqlens"]) - 1)
+    with pytest.raises(sb.SparseBalError) as e:
+        sb.Problem(**args)
+    assert f"error {code}:" in str(e.value) and len(str(e.value)) > 25
+
+
+def test_empty_problem_layout():
+    pb = sb.Problem([0], [], 4, 2, 64)
+    assert pb.layout.num_qblocks == 0 and pb.layout.sel_nnz == 0
+    pb = sb.Problem([0, 0, 0], [1, 1], 4, 2, 64)
+    assert pb.layout.num_qblocks == 0 and pb.layout.sel_nnz == 0
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(sb, "_lib", None)
+    monkeypatch.setattr(sb, "LIB_PATH", "/nonexistent/libsparsebal.so")
+    with pytest.raises(sb.SparseBalError):
+        sb.sb_version()
