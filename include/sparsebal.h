@@ -135,13 +135,22 @@ int sb_sparse_attn_bwd(const sb_problem *p, const void *q, const void *k, const 
                        const float *lse, const void *d_o, const int32_t *sel_rowptr, const int32_t *sel_idx,
                        const void *plan, void *dq, void *dk, void *dv, void *ws, void *stream);
 
-/* Instrumentation.  When enabled (flag != 0) the attention kernels add, for every workgroup, its
- * run time in ticks of the 100 MHz constant clock to a per-compute-unit slot inside `ws`;
- * sb_read_cu_busy copies the SB_CU_SLOTS slots of the last forward or backward call that used `ws`
- * to host memory (it synchronises the stream). */
+/* Instrumentation (measurement only; off by default).  `flag` is a bit set:
+ *   SB_INSTR_CU_BUSY  the attention kernels add, for every workgroup, its run time in ticks of the
+ *                     100 MHz constant clock to a per-compute-unit slot inside `ws`; sb_read_cu_busy
+ *                     copies the SB_CU_SLOTS slots of the last forward or backward call that used
+ *                     `ws` to host memory (it synchronises the stream).  This is the per-CU busy time
+ *                     whose max/mean is the imbalance measure of the paper's Eq. 11 applied to CUs.
+ *   SB_INSTR_KERNEL_EVENTS  every kernel launch is bracketed by HIP events on the launch stream;
+ *                     sb_read_kernel_times waits for them, writes per-kernel total milliseconds and
+ *                     launch counts (SB_NUM_KERNELS entries each, host) and resets the record. */
 #define SB_CU_SLOTS 512
+#define SB_INSTR_CU_BUSY 1
+#define SB_INSTR_KERNEL_EVENTS 2
+#define SB_NUM_KERNELS 8 /* pool, score, topk, plan, fwd, bwd_prep, bwd_dq, bwd_dkv */
 int sb_set_instrumentation(int flag);
 int sb_read_cu_busy(const void *ws, uint64_t *busy_out_host, void *stream);
+int sb_read_kernel_times(double *total_ms_host, int64_t *launches_host);
 
 const char *sb_last_error(void);
 const char *sb_version(void);

@@ -21,7 +21,7 @@ SB_SELECT_PER_QHEAD, SB_SELECT_PER_KVGROUP = 0, 1
 SB_CU_SLOTS = 512
 
 EXPORTS = ["sb_get_layout", "sb_keep_ratio_to_topk", "sb_sel_rowptr_host", "sb_block_scores", "sb_select_topk",
-           "sb_plan_worklist", "sb_sparse_attn_fwd", "sb_sparse_attn_bwd", "sb_set_instrumentation", "sb_read_cu_busy",
+           "sb_plan_worklist", "sb_sparse_attn_fwd", "sb_sparse_attn_bwd", "sb_set_instrumentation", "sb_read_cu_busy", "sb_read_kernel_times",
            "sb_last_error", "sb_version"]
 
 
@@ -167,8 +167,20 @@ def sb_sparse_attn_bwd(pb: Problem, q, k, v, o, lse, d_o, sel_rowptr, sel_idx, p
     return dq, dk, dv
 
 
-def sb_set_instrumentation(flag: bool):
-    _check(lib().sb_set_instrumentation(int(bool(flag))))
+SB_INSTR_CU_BUSY, SB_INSTR_KERNEL_EVENTS = 1, 2
+KERNEL_NAMES = ["pool", "score", "topk", "plan", "fwd", "bwd_prep", "bwd_dq", "bwd_dkv"]
+
+
+def sb_set_instrumentation(flag: int):
+    _check(lib().sb_set_instrumentation(int(flag)))
+
+
+def sb_read_kernel_times():
+    """{kernel: (total_ms, launches)} since the last call."""
+    ms = np.zeros(len(KERNEL_NAMES), dtype=np.float64)
+    cnt = np.zeros(len(KERNEL_NAMES), dtype=np.int64)
+    _check(lib().sb_read_kernel_times(_ptr(ms), _ptr(cnt)))
+    return {n: (float(ms[i]), int(cnt[i])) for i, n in enumerate(KERNEL_NAMES)}
 
 
 def sb_read_cu_busy(ws) -> np.ndarray:

@@ -287,6 +287,7 @@ static int launch_bwd(const Geo& g, const AttnParams& P, hipStream_t st) {
   AttnParams Pq = P;
   Pq.work = P.work;  // forward work list
   dim3 grid((unsigned)(g.Hs * g.NQB), (unsigned)parts), block((unsigned)(128 * hpp));
+  KernelTimer kt(K_BWD_DQ, st);
   if (hpp == 1) hipLaunchKernelGGL((attn_bwd_dq_kernel<D, F32, 128>), grid, block, 0, st, Pq);
   else if (hpp == 2) hipLaunchKernelGGL((attn_bwd_dq_kernel<D, F32, 256>), grid, block, 0, st, Pq);
   else hipLaunchKernelGGL((attn_bwd_dq_kernel<D, F32, 512>), grid, block, 0, st, Pq);
@@ -304,6 +305,7 @@ static int launch_dkv(const Geo& g, const AttnParams& P, hipStream_t st) {
     attr_set = true;
   }
   dim3 grid((unsigned)(g.Hkv * g.NQB)), block(128);
+  KernelTimer kt(K_BWD_DKV, st);
   hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, F32>), grid, block, smem, st, P);
   SB_LAUNCH_CHECK("attn_bwd_dkv_kernel");
   return SB_OK;
@@ -351,15 +353,18 @@ extern "C" int sb_sparse_attn_bwd(const sb_problem* p, const void* q, const void
   P.scale = g.softmax_scale; P.scale_log2e = g.softmax_scale * 1.4426950408889634f;
   P.out_f32 = f32;
   P.cu_busy = nullptr;
-  if (g_instrument) {
+  if (g_instrument & 1) {
     SB_CHECK_HIP(hipMemsetAsync(wb + wo.cu_busy, 0, sizeof(uint64_t) * SB_CU_SLOTS, st));
     P.cu_busy = (unsigned long long*)(wb + wo.cu_busy);
   }
   const int64_t rows = (int64_t)g.T * g.Hq;
   const int rows_per_wg = 256 / (g.D / 8);
   dim3 pgrid((unsigned)((rows + rows_per_wg - 1) / rows_per_wg));
+  {
+  KernelTimer kt(K_BWD_PREP, st);
   if (f32) hipLaunchKernelGGL(bwd_prep_kernel<true>, pgrid, dim3(256), 0, st, o, P.d_o, rows, g.T, g.Hq, g.D, drow);
   else hipLaunchKernelGGL(bwd_prep_kernel<false>, pgrid, dim3(256), 0, st, o, P.d_o, rows, g.T, g.Hq, g.D, drow);
+  }
   SB_LAUNCH_CHECK("bwd_prep_kernel");
 
   AttnParams Pq = P, Pk = P;

@@ -180,13 +180,14 @@ extern "C" int sb_sparse_attn_fwd(const sb_problem* p, const void* q, const void
   P.scale = g.softmax_scale; P.scale_log2e = g.softmax_scale * 1.4426950408889634f;
   P.out_f32 = g.dtype == SB_F32;
   P.cu_busy = nullptr;
-  if (g_instrument) {
+  if (g_instrument & 1) {
     SB_CHECK_HIP(hipMemsetAsync(wb + wo.cu_busy, 0, sizeof(uint64_t) * SB_CU_SLOTS, st));
     P.cu_busy = (unsigned long long*)(wb + wo.cu_busy);
   }
   const int G = g.mode == SB_SELECT_PER_QHEAD ? 1 : g.G;
   const int parts = (G + 3) / 4, hpp = (G + parts - 1) / parts;  // query heads per workgroup <= 4
   dim3 grid((unsigned)(g.Hs * g.NQB), (unsigned)parts), block((unsigned)(128 * hpp));
+  KernelTimer kt(K_FWD, st);
 #define SB_FWD_LAUNCH(DD, FF)                                                                         \
   do {                                                                                                \
     if (hpp == 1) hipLaunchKernelGGL((attn_fwd_kernel<DD, FF, 128>), grid, block, 0, st, P);          \

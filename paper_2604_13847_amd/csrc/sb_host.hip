@@ -10,6 +10,24 @@ namespace sb {
 static thread_local char g_err[512] = "";
 int g_instrument = 0;
 
+struct EventPair { hipEvent_t a, b; };
+static std::vector<EventPair> g_events[K_NUM];
+
+KernelTimer::KernelTimer(int slot_, hipStream_t st_) : slot(slot_), st(st_) {
+  if (!(g_instrument & 2)) return;
+  hipEvent_t a;
+  if (hipEventCreate(&a) != hipSuccess) return;
+  (void)hipEventRecord(a, st);
+  start = (void*)a;
+}
+KernelTimer::~KernelTimer() {
+  if (!start) return;
+  hipEvent_t b;
+  if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy((hipEvent_t)start); return; }
+  (void)hipEventRecord(b, st);
+  g_events[slot].push_back({(hipEvent_t)start, b});
+}
+
 void set_error(const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
@@ -271,7 +289,23 @@ int sb_sel_rowptr_host(const sb_problem* p, int32_t* rowptr) {
   return SB_OK;
 }
 
-int sb_set_instrumentation(int flag) { g_instrument = flag != 0; return SB_OK; }
+int sb_set_instrumentation(int flag) { g_instrument = flag & 3; return SB_OK; }
+
+int sb_read_kernel_times(double* total_ms, int64_t* launches) {
+  if (!total_ms || !launches) { set_error("null argument"); return SB_ERR_INVALID_ARG; }
+  for (int k = 0; k < K_NUM; ++k) {
+    total_ms[k] = 0.0; launches[k] = 0;
+    for (auto& e : g_events[k]) {
+      float ms = 0.f;
+      SB_CHECK_HIP(hipEventSynchronize(e.b));
+      SB_CHECK_HIP(hipEventElapsedTime(&ms, e.a, e.b));
+      total_ms[k] += ms; launches[k] += 1;
+      (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b);
+    }
+    g_events[k].clear();
+  }
+  return SB_OK;
+}
 
 int sb_read_cu_busy(const void* ws, uint64_t* out, void* stream) {
   if (!ws || !out) { set_error("null argument"); return SB_ERR_INVALID_ARG; }

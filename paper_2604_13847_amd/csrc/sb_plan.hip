@@ -122,6 +122,7 @@ extern "C" int sb_plan_worklist(const sb_problem* p, const int32_t* sel_rowptr, 
   int32_t* bins = (int32_t*)(base + po.bins);
   uint32_t* bitmap = (uint32_t*)(base + po.bitmap);
   const int64_t rows = (int64_t)g.Hs * g.NQB, ncol = (int64_t)g.Hkv * g.NQB;
+  KernelTimer kt(K_PLAN, st);
   // colcost, work_bwd, bins and bitmap are adjacent: clear colcost, bins and bitmap
   SB_CHECK_HIP(hipMemsetAsync(colcost, 0, po.bytes - po.colcost, st));
   hipLaunchKernelGGL(plan_fwd_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, t.qb_off, t.kclamp, t.qb_seq,

@@ -161,12 +161,15 @@ extern "C" int sb_block_scores(const sb_problem* p, const void* q, const void* k
   float* kbar = (float*)(b + align_up(sizeof(float) * (size_t)g.NQB * g.Hq * g.D));
   const int qcols = g.Hq * g.D, kcols = g.Hkv * g.D;
   dim3 gq((unsigned)g.NQB, (unsigned)((qcols + 1023) / 1024)), gk((unsigned)g.NQB, (unsigned)((kcols + 1023) / 1024));
+  {
+  KernelTimer kt(K_POOL, st);
   if (g.dtype == SB_F32) {
     hipLaunchKernelGGL(pool_kernel<true>, gq, dim3(256), 0, st, q, qcols, t.cu, t.qb_off, t.qb_seq, g.B, qbar);
     hipLaunchKernelGGL(pool_kernel<true>, gk, dim3(256), 0, st, k, kcols, t.cu, t.qb_off, t.qb_seq, g.B, kbar);
   } else {
     hipLaunchKernelGGL(pool_kernel<false>, gq, dim3(256), 0, st, q, qcols, t.cu, t.qb_off, t.qb_seq, g.B, qbar);
     hipLaunchKernelGGL(pool_kernel<false>, gk, dim3(256), 0, st, k, kcols, t.cu, t.qb_off, t.qb_seq, g.B, kbar);
+  }
   }
   SB_LAUNCH_CHECK("pool_kernel");
   if (kbar_out)
@@ -179,6 +182,7 @@ extern "C" int sb_block_scores(const sb_problem* p, const void* q, const void* k
     tiles += (n + 63) / 64;
   }
   dim3 gs((unsigned)tiles, (unsigned)g.Hs);
+  KernelTimer kt(K_SCORE, st);
   if (g.D == 128)
     hipLaunchKernelGGL(score_kernel<128>, gs, dim3(256), 0, st, qbar, kbar, t.cu, t.qb_off, t.sc_off, g.S, g.Hq, g.Hkv,
                        g.Hs, g.G, g.mode, g.score_scale, scores_out);

@@ -147,6 +147,7 @@ extern "C" int sb_select_topk(const sb_problem* p, const float* scores, int32_t*
       attr_set = true;
     }
   }
+  KernelTimer kt(K_TOPK, st);
   hipLaunchKernelGGL(topk_kernel, grid, dim3(256), smem, st, scores, t.qb_off, t.sc_off, t.row_base, t.kclamp, t.qb_seq,
                      g.NQB, g.Hs, g.nnz_unit, sel_rowptr_out, sel_idx_out);
   SB_LAUNCH_CHECK("topk_kernel");

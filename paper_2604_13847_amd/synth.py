@@ -51,16 +51,28 @@ def uniform01(seed: int, tid: int, start: int, count: int) -> np.ndarray:
     return ((z >> np.uint64(11)).astype(np.float64) + 0.5) * (1.0 / 9007199254740992.0)
 
 
-def normal_f32(seed: int, tid: int, count: int, chunk: int = 1 << 24) -> np.ndarray:
-    """`count` i.i.d. N(0,1) values as float32 (computed in float64, then rounded)."""
-    out = np.empty(count, dtype=np.float32)
+def _normal_chunk(args):
+    seed, tid, s, n, out = args
     inv = 1.0 / 16777216.0
-    for s in range(0, count, chunk):
-        n = min(chunk, count - s)
-        z = raw_u64(seed, tid, s, n)
-        u1 = ((z >> np.uint64(40)).astype(np.float64) + 0.5) * inv
-        u2 = ((z & np.uint64(0xFFFFFF)).astype(np.float64) + 0.5) * inv
-        out[s:s + n] = (np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)).astype(np.float32)
+    z = raw_u64(seed, tid, s, n)
+    u1 = ((z >> np.uint64(40)).astype(np.float64) + 0.5) * inv
+    u2 = ((z & np.uint64(0xFFFFFF)).astype(np.float64) + 0.5) * inv
+    out[s:s + n] = (np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)).astype(np.float32)
+
+
+def normal_f32(seed: int, tid: int, count: int, chunk: int = 1 << 21) -> np.ndarray:
+    """`count` i.i.d. N(0,1) values as float32 (computed in float64, then rounded).
+    Chunks are independent (counter-based), so they are filled by a small thread pool."""
+    out = np.empty(count, dtype=np.float32)
+    jobs = [(seed, tid, s, min(chunk, count - s), out) for s in range(0, count, chunk)]
+    if len(jobs) <= 1:
+        for j in jobs:
+            _normal_chunk(j)
+        return out
+    from concurrent.futures import ThreadPoolExecutor
+    import os
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+        list(ex.map(_normal_chunk, jobs))
     return out
 
 

@@ -1,0 +1,59 @@
+"""GPU parity at the benchmark's full size (configs[1]: packed 32768 tokens, 32/8 heads, D=128) in
+the launch configuration bench.py times.  The CPU checker evaluates sampled outputs one by one:
+score rows, query rows (O, LSE, dQ) and whole key blocks (dK, dV); the selection is compared in full."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import Run, check_close, to_host_f32
+from oracle import oracle as orc
+from paper_2604_13847_amd import binding as sb
+from paper_2604_13847_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_config2_sampled(mode):
+    w = synth.config2(0)
+    r = Run(w, mode)
+    po, lay = r.opb, r.pb.layout
+    rng = np.random.default_rng(5)
+    got_scores = r.scores.cpu().numpy()[: lay.scores_elems]
+    # scores: sampled rows
+    q, k, v, do = r.oracle_inputs()
+    for _ in range(12):
+        s = int(rng.integers(0, w.S)); hs = int(rng.integers(0, po.Hs)); i = int(rng.integers(0, po.nblk[s]))
+        ref = orc.block_scores_row(po, q, k, r.scale, s, hs, i)
+        n = po.nblk[s]
+        got = got_scores[po.score_off[s] + (hs * n + i) * n: po.score_off[s] + (hs * n + i + 1) * n]
+        assert np.array_equal(np.isneginf(got), np.isneginf(ref))
+        fin = np.isfinite(ref)
+        if fin.any():
+            assert np.abs(got[fin] - ref[fin]).max() <= 2e-5 * max(1e-3, np.abs(ref[fin]).max())
+    # selection: all rows, bit-exact on the GPU's scores
+    rp, idx = orc.select_topk(po, got_scores, r.topk)
+    assert np.array_equal(rp, r.rowptr_h) and np.array_equal(idx, r.idx_h)
+    # plan: every item once, longest first
+    pv = sb.plan_views(r.pb, r.plan)
+    assert np.array_equal(np.sort(pv["work_fwd"]), np.arange(lay.sel_rows))
+    assert np.all(np.diff(np.diff(r.rowptr_h)[pv["work_fwd"]]) <= 0)
+    assert np.array_equal(np.sort(pv["work_bwd"]), np.arange(w.Hkv * lay.num_qblocks))
+    assert np.all(np.diff(np.minimum(pv["colcost"][pv["work_bwd"]], 4095)) <= 0)
+    assert pv["colcost"].sum() == lay.sel_nnz * (1 if mode == 0 else w.Hq // w.Hkv)
+    # sampled query rows, spread over sequences, including first/last rows of sequences
+    toks = np.concatenate([rng.integers(0, w.T, size=160), w.cu[:-1], w.cu[1:] - 1]).astype(np.int32)
+    heads = rng.integers(0, w.Hq, size=toks.size).astype(np.int32)
+    O, LSE, dQ = orc.attn_rows(po, q, k, v, do, r.rowptr_h, r.idx_h, r.scale, toks, heads)
+    ti, hi = torch.from_numpy(toks.astype(np.int64)), torch.from_numpy(heads.astype(np.int64))
+    print("O", check_close("O", to_host_f32(r.o.cpu()[ti, hi]), O), "dQ", check_close("dQ", to_host_f32(r.dq.cpu()[ti, hi]), dQ))
+    assert np.abs(r.lse.cpu().numpy()[heads, toks] - LSE).max() <= 1e-2
+    # sampled key blocks: first block of the longest sequence (heaviest column), a middle one, a ragged tail
+    s_long = int(np.argmax(po.nblk))
+    picks = [(s_long, 0, 0), (s_long, w.Hkv - 1, po.nblk[s_long] // 2), (s_long, 1, po.nblk[s_long] - 1), (0, 2, 1)]
+    for (s, g, j) in picks:
+        dK, dV = orc.attn_bwd_kvblock(po, q, k, v, do, r.rowptr_h, r.idx_h, r.scale, s, g, j)
+        a = int(w.cu[s]) + j * 64
+        b = min(a + 64, int(w.cu[s + 1]))
+        print((s, g, j), "dK", check_close("dK", to_host_f32(r.dk[a:b, g]), dK[: b - a]),
+              "dV", check_close("dV", to_host_f32(r.dv[a:b, g]), dV[: b - a]), flush=True)
