@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsparsebal.so")
 SOURCES = ["sb_host.hip", "sb_scores.hip", "sb_topk.hip", "sb_plan.hip", "sb_attn_fwd.hip", "sb_attn_bwd.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-variable", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+         "-Wno-unused-variable", "-Wno-inline-asm", "-Wno-pass-failed", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
 
 def build_lib(verbose: bool = False, extra=()) -> str:

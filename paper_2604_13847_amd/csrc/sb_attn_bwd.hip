@@ -40,16 +40,19 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(const void* __restrict__ 
 }
 
 // ---------------------------------------------------------------------------------------------
+// Query-major dQ kernel.  Same work items and strips as the forward.  The K and V tiles of the
+// selected blocks are double-buffered in LDS as whole tiles: while tile t is consumed, tile t+1 is
+// in flight (asynchronous global->LDS loads).  K is read row-wise for S^T = K Q^T and through the
+// transposing LDS read for dQ^T += K^T dS^T; V is read row-wise for dP^T = V dO^T.
 template <int D, bool OUT_F32, int MAXT>
-__global__ __launch_bounds__(MAXT) void attn_bwd_dq_kernel(AttnParams P) {
-  constexpr int KLD = D + 8, TLD = 64 + 8;
-  __shared__ __attribute__((aligned(16))) bf16 Ks[64 * KLD];
-  __shared__ __attribute__((aligned(16))) bf16 Vs[64 * KLD];
-  __shared__ __attribute__((aligned(16))) bf16 Kt[D * TLD];
+__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(MAXT >= 256 ? 2 : 1))) void attn_bwd_dq_kernel(AttnParams P) {
+  __shared__ __attribute__((aligned(1024))) bf16 tiles[2][2][64 * D];  // [buffer][K, V]
+  constexpr int kJ = 256;
+  __shared__ int jbuf[kJ];
   BusyTimer timer;
   timer.start(P);
   const int tid = threadIdx.x, nthr = blockDim.x;
-  const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
   const int64_t row = P.work[blockIdx.x];
   const int hs = (int)(row / P.NQB);
   const int qb = (int)(row - (int64_t)hs * P.NQB);
@@ -64,6 +67,20 @@ __global__ __launch_bounds__(MAXT) void attn_bwd_dq_kernel(AttnParams P) {
   const int qloc = strip * 32 + l32;
   const bool qvalid = head_ok && i * 64 + qloc < L;
   const int64_t tq = seq0 + i * 64 + qloc;
+  const int e0 = P.rowptr[row], ntiles = P.rowptr[row + 1] - e0;
+
+  auto stage_indices = [&](int t0) {
+    __syncthreads();
+    for (int a = tid; a < kJ; a += nthr) jbuf[a] = t0 + a < ntiles ? P.idx[e0 + t0 + a] : 0;
+    __syncthreads();
+  };
+  auto issue = [&](int t) {
+    const int j = jbuf[t % kJ];
+    const int64_t kv0 = seq0 + (int64_t)j * 64;
+    const int kvalid = min(64, L - j * 64);
+    async_tile_load<D>(tiles[t & 1][0], P.k, kv0, kvalid, P.Hkv, g, wave, lane);
+    async_tile_load<D>(tiles[t & 1][1], P.v, kv0, kvalid, P.Hkv, g, wave, lane);
+  };
 
   bf16x8 qf[D / 16], dof[D / 16];
   float lse2 = __builtin_inff(), dr = 0.f;  // invalid rows: P = exp2(x - inf) = 0
@@ -80,34 +97,34 @@ __global__ __launch_bounds__(MAXT) void attn_bwd_dq_kernel(AttnParams P) {
       dr = P.drow[(int64_t)h * P.T + tq];
     }
   }
+  stage_indices(0);
+  // everything loaded so far must have landed before the tile loads start (see the forward kernel)
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) asm volatile("" : "+v"(qf[ks]), "+v"(dof[ks]));
+  asm volatile("" : "+v"(lse2), "+v"(dr));
+  issue(0);
+
   f32x16 dqacc[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt) dqacc[dt] = zero16();
 
-  const int e0 = P.rowptr[row], e1 = P.rowptr[row + 1];
-  for (int e = e0; e < e1; ++e) {
-    const int j = P.idx[e];
-    const int64_t kv0 = seq0 + (int64_t)j * 64;
-    const int kvalid = min(64, L - j * 64);
-    __syncthreads();
-    load_tile_transposed<D, KLD, TLD>(Kt, Ks, P.k, kv0, kvalid, P.Hkv, g, tid, nthr);
-    load_tile_rowmajor<D, KLD>(Vs, P.v, kv0, kvalid, P.Hkv, g, tid, nthr);
-    __syncthreads();
-    const bool diag = j == i;
+  for (int t = 0; t < ntiles; ++t) {
+    const bool more = t + 1 < ntiles;
+    if (more && (t + 1) % kJ == 0) stage_indices(t + 1);
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();  // tile t has landed for everyone; everyone is done with tile t-1
+    if (more) issue(t + 1);
+    const bf16* Ks = tiles[t & 1][0];
+    const bf16* Vs = tiles[t & 1][1];
+    const bool diag = t == ntiles - 1;
     bf16x8 dsb[4];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
       f32x16 sacc = zero16(), dpacc = zero16();
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) {
-        bf16x8 a = *(const bf16x8*)(Ks + (32 * mt + l32) * KLD + 16 * ks + 8 * hf);
-        sacc = mfma32(a, qf[ks], sacc);
-      }
+      for (int ks = 0; ks < D / 16; ++ks) sacc = mfma32(lds_row8<D>(Ks, 32 * mt + l32, 2 * ks + hf), qf[ks], sacc);
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) {
-        bf16x8 a = *(const bf16x8*)(Vs + (32 * mt + l32) * KLD + 16 * ks + 8 * hf);
-        dpacc = mfma32(a, dof[ks], dpacc);
-      }
+      for (int ks = 0; ks < D / 16; ++ks) dpacc = mfma32(lds_row8<D>(Vs, 32 * mt + l32, 2 * ks + hf), dof[ks], dpacc);
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         float pv = fast_exp2(sacc[v] * P.scale_log2e - lse2);
@@ -118,10 +135,7 @@ __global__ __launch_bounds__(MAXT) void attn_bwd_dq_kernel(AttnParams P) {
 #pragma unroll
     for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        bf16x8 a = *(const bf16x8*)(Kt + (32 * dt + l32) * TLD + 16 * kk + 8 * hf);
-        dqacc[dt] = mfma32(a, dsb[kk], dqacc[dt]);
-      }
+      for (int kk = 0; kk < 4; ++kk) dqacc[dt] = mfma32(lds_tr_operand<D>(Ks, kk, dt, lane), dsb[kk], dqacc[dt]);
   }
   if (qvalid) {
     const int64_t obase = (tq * P.Hq + h) * D;
@@ -145,21 +159,21 @@ __global__ __launch_bounds__(MAXT) void attn_bwd_dq_kernel(AttnParams P) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Key-major kernel: 2 wavefronts, each owns 32 keys of the block.
+// Key-major dK/dV kernel: 2 wavefronts, each owns 32 keys of key block (s, g, j) and keeps their
+// K and V rows in registers.  The Q and dO tiles (plus LSE and Dr) of the query blocks that kept j
+// are double-buffered in LDS by asynchronous loads; both are read row-wise (S = Q K^T, dP = dO V^T)
+// and through the transposing LDS read (dV += P^T dO, dK += dS^T Q).
+// The column's query blocks come from the transpose bitmap, staged in LDS 64 words (2048 query
+// blocks) per selection head at a time and walked in ascending order.
 template <int D, bool OUT_F32>
 __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(AttnParams P) {
-  constexpr int QLD = D + 8, TLD = 64 + 8;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  bf16* Qs = (bf16*)smem;          // [64][QLD]
-  bf16* dOs = Qs + 64 * QLD;       // [64][QLD]
-  bf16* Qt = dOs + 64 * QLD;       // [D][TLD]
-  bf16* dOt = Qt + D * TLD;        // [D][TLD]
-  float* lse_s = (float*)(dOt + D * TLD);  // [64] LSE * log2(e), +inf for rows past the sequence end
-  float* dr_s = lse_s + 64;                // [64]
+  __shared__ __attribute__((aligned(1024))) bf16 tiles[2][2][64 * D];  // [buffer][Q, dO]
+  __shared__ __attribute__((aligned(256))) float rowstat[2][2][64];    // [buffer][LSE, Dr]
+  __shared__ uint32_t bm_s[8][64];
   BusyTimer timer;
   timer.start(P);
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
   const int64_t col = P.work[blockIdx.x];  // g * NQB + global block index
   const int g = (int)(col / P.NQB);
   const int qbj = (int)(col - (int64_t)g * P.NQB);
@@ -189,71 +203,96 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(AttnParams P) {
   const int words = (n + 31) >> 5;
   const int nsel = P.mode == SB_SELECT_PER_QHEAD ? P.G : 1;   // bitmap columns to walk
   const int hpe = P.mode == SB_SELECT_PER_QHEAD ? 1 : P.G;    // query heads per set bit
-  for (int a = 0; a < nsel; ++a) {
-    const int hs = P.mode == SB_SELECT_PER_QHEAD ? g * P.G + a : g;
-    const uint32_t* bm = P.bitmap + (int64_t)P.Hs * P.bm_off[s] + ((int64_t)hs * n + j) * words;
-    for (int wi = j >> 5; wi < words; ++wi) {
-      uint32_t bits = bm[wi];
-      while (bits) {
-        const int b = __builtin_ctz(bits);
-        bits &= bits - 1;
-        const int i = 32 * wi + b;
-        const int64_t q0 = seq0 + (int64_t)i * 64;
-        const int qvalid = min(64, L - i * 64);
-        const bool diag = i == j;
-        for (int hb = 0; hb < hpe; ++hb) {
-          const int h = P.mode == SB_SELECT_PER_QHEAD ? hs : g * P.G + hb;
-          __syncthreads();
-          load_tile_transposed<D, QLD, TLD>(Qt, Qs, P.q, q0, qvalid, P.Hq, h, tid, 128);
-          load_tile_transposed<D, QLD, TLD>(dOt, dOs, P.d_o, q0, qvalid, P.Hq, h, tid, 128);
-          if (tid < 64) {
-            const bool ok = tid < qvalid;
-            lse_s[tid] = ok ? P.lse[(int64_t)h * P.T + q0 + tid] * 1.4426950408889634f : __builtin_inff();
-            dr_s[tid] = ok ? P.drow[(int64_t)h * P.T + q0 + tid] : 0.f;
+
+  auto issue = [&](int buf, int i, int h) {
+    const int64_t q0 = seq0 + (int64_t)i * 64;
+    const int qv = min(64, L - i * 64);
+    async_tile_load<D>(tiles[buf][0], P.q, q0, qv, P.Hq, h, wave, lane);
+    async_tile_load<D>(tiles[buf][1], P.d_o, q0, qv, P.Hq, h, wave, lane);
+    // 64 LSE and 64 Dr values: one 4-byte load per lane, wavefront 0 takes LSE and wavefront 1 Dr
+    const float* src = (wave == 0 ? P.lse : P.drow) + (int64_t)h * P.T + q0 + min(lane, qv - 1);
+    dma4(src, lds_offset(rowstat[buf][wave]));
+  };
+
+  for (int w0 = (j >> 5) & ~63; w0 < words; w0 += 64) {  // chunks of 64 bitmap words
+    const int wn = min(64, words - w0);
+    __syncthreads();
+    for (int a = tid; a < nsel * 64; a += 128) {
+      const int sel = a >> 6, w = a & 63;
+      const int hs = P.mode == SB_SELECT_PER_QHEAD ? g * P.G + sel : g;
+      bm_s[sel][w] = w < wn ? P.bitmap[(int64_t)P.Hs * P.bm_off[s] + ((int64_t)hs * n + j) * words + w0 + w] : 0u;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) asm volatile("" : "+v"(kf[ks]), "+v"(vf[ks]));
+    // iterator over (query block i, query head h) in the order (selection head, i ascending, head)
+    int it_sel = 0, it_w = -1, it_hb = 0, it_i = 0;
+    uint32_t it_bits = 0;
+    auto next = [&](int& i, int& h) -> bool {
+      if (it_hb > 0 && it_hb < hpe) { i = it_i; h = g * P.G + it_hb; ++it_hb; return true; }
+      while (true) {
+        if (it_bits) {
+          const int b = __builtin_ctz(it_bits);
+          it_bits &= it_bits - 1;
+          it_i = 32 * (w0 + it_w) + b;
+          i = it_i;
+          h = P.mode == SB_SELECT_PER_QHEAD ? g * P.G + it_sel : g * P.G;
+          it_hb = 1;
+          return true;
+        }
+        ++it_w;
+        if (it_w >= wn) { it_w = 0; ++it_sel; }
+        if (it_sel >= nsel) return false;
+        it_bits = __builtin_amdgcn_readfirstlane(bm_s[it_sel][it_w]);
+      }
+    };
+    int ci, ch, ni = 0, nh = 0;
+    bool have = next(ci, ch);
+    if (have) issue(0, ci, ch);
+    for (int t = 0; have; ++t) {
+      const bool more = next(ni, nh);
+      wait_vmcnt<0>();
+      __builtin_amdgcn_s_barrier();
+      if (more) issue((t + 1) & 1, ni, nh);
+      const bf16* Qs = tiles[t & 1][0];
+      const bf16* dOs = tiles[t & 1][1];
+      const float* lse_s = rowstat[t & 1][0];
+      const float* dr_s = rowstat[t & 1][1];
+      const int qv = min(64, L - ci * 64);
+      const bool diag = ci == j;
+      bf16x8 pa[4], dsa[4];
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+        f32x16 sacc = zero16(), dpacc = zero16();
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) sacc = mfma32(lds_row8<D>(Qs, 32 * qt + l32, 2 * ks + hf), kf[ks], sacc);
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) dpacc = mfma32(lds_row8<D>(dOs, 32 * qt + l32, 2 * ks + hf), vf[ks], dpacc);
+#pragma unroll
+        for (int vg = 0; vg < 4; ++vg) {
+          const int qr = 32 * qt + 8 * vg + 4 * hf;  // query rows qr..qr+3 are registers 4vg..4vg+3
+          const float4 ls = *(const float4*)(lse_s + qr);
+          const float4 dd = *(const float4*)(dr_s + qr);
+          const float lsv[4] = {ls.x, ls.y, ls.z, ls.w};
+          const float ddv[4] = {dd.x, dd.y, dd.z, dd.w};
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const int v = 4 * vg + c;
+            float pv = fast_exp2(sacc[v] * P.scale_log2e - lsv[c] * 1.4426950408889634f);
+            if ((diag && kloc > qr + c) || qr + c >= qv) pv = 0.f;
+            pa[2 * qt + (v >> 3)][v & 7] = (bf16)pv;
+            dsa[2 * qt + (v >> 3)][v & 7] = (bf16)(pv * (dpacc[v] - ddv[c]));
           }
-          __syncthreads();
-          bf16x8 pa[4], dsa[4];
-#pragma unroll
-          for (int qt = 0; qt < 2; ++qt) {
-            f32x16 sacc = zero16(), dpacc = zero16();
-#pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) {
-              bf16x8 qa = *(const bf16x8*)(Qs + (32 * qt + l32) * QLD + 16 * ks + 8 * hf);
-              sacc = mfma32(qa, kf[ks], sacc);
-            }
-#pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) {
-              bf16x8 da = *(const bf16x8*)(dOs + (32 * qt + l32) * QLD + 16 * ks + 8 * hf);
-              dpacc = mfma32(da, vf[ks], dpacc);
-            }
-#pragma unroll
-            for (int vg = 0; vg < 4; ++vg) {
-              const int qr = 32 * qt + 8 * vg + 4 * hf;  // query rows qr..qr+3 are registers 4vg..4vg+3
-              const float4 ls = *(const float4*)(lse_s + qr);
-              const float4 dd = *(const float4*)(dr_s + qr);
-              const float lsv[4] = {ls.x, ls.y, ls.z, ls.w};
-              const float ddv[4] = {dd.x, dd.y, dd.z, dd.w};
-#pragma unroll
-              for (int c = 0; c < 4; ++c) {
-                const int v = 4 * vg + c;
-                float pv = fast_exp2(sacc[v] * P.scale_log2e - lsv[c]);
-                if (diag && kloc > qr + c) pv = 0.f;
-                pa[2 * qt + (v >> 3)][v & 7] = (bf16)pv;
-                dsa[2 * qt + (v >> 3)][v & 7] = (bf16)(pv * (dpacc[v] - ddv[c]));
-              }
-            }
-          }
-#pragma unroll
-          for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-              bf16x8 db = *(const bf16x8*)(dOt + (32 * dt + l32) * TLD + 16 * kk + 8 * hf);
-              dvacc[dt] = mfma32(pa[kk], db, dvacc[dt]);
-              bf16x8 qbv = *(const bf16x8*)(Qt + (32 * dt + l32) * TLD + 16 * kk + 8 * hf);
-              dkacc[dt] = mfma32(dsa[kk], qbv, dkacc[dt]);
-            }
         }
       }
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          dvacc[dt] = mfma32(pa[kk], lds_tr_operand<D>(dOs, kk, dt, lane), dvacc[dt]);
+          dkacc[dt] = mfma32(dsa[kk], lds_tr_operand<D>(Qs, kk, dt, lane), dkacc[dt]);
+        }
+      have = more; ci = ni; ch = nh;
     }
   }
   // C layout: column = d (32dt + l32), register v = key row c_row(v, hf) of this wavefront's strip
@@ -280,7 +319,6 @@ int convert_f32_to_bf16(const void* src, void* dst, int64_t n, hipStream_t st);
 
 template <int D, bool F32>
 static int launch_bwd(const Geo& g, const AttnParams& P, hipStream_t st) {
-  constexpr int QLD = D + 8, TLD = 64 + 8;
   // query-major dQ
   const int G = g.mode == SB_SELECT_PER_QHEAD ? 1 : g.G;
   const int parts = (G + 3) / 4, hpp = (G + parts - 1) / parts;
@@ -297,16 +335,9 @@ static int launch_bwd(const Geo& g, const AttnParams& P, hipStream_t st) {
 
 template <int D, bool F32>
 static int launch_dkv(const Geo& g, const AttnParams& P, hipStream_t st) {
-  constexpr int QLD = D + 8, TLD = 64 + 8;
-  const size_t smem = sizeof(bf16) * (size_t)(2 * 64 * QLD + 2 * D * TLD) + sizeof(float) * 128;
-  static bool attr_set = false;
-  if (!attr_set) {
-    SB_CHECK_HIP(hipFuncSetAttribute((const void*)attn_bwd_dkv_kernel<D, F32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    attr_set = true;
-  }
   dim3 grid((unsigned)(g.Hkv * g.NQB)), block(128);
   KernelTimer kt(K_BWD_DKV, st);
-  hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, F32>), grid, block, smem, st, P);
+  hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, F32>), grid, block, 0, st, P);
   SB_LAUNCH_CHECK("attn_bwd_dkv_kernel");
   return SB_OK;
 }

@@ -106,6 +106,91 @@ __device__ inline void load_tile_transposed(bf16* dst_t, bf16* dst_rm, const bf1
   }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Asynchronous tile staging.  A 64 x D bf16 tile lives in LDS unpadded (row r at byte r*2D), with
+// the 16-byte chunks of each row permuted by chunk_swizzle(r): chunk c of row r sits at chunk
+// c ^ chunk_swizzle(r).  The permutation makes both access patterns of the MFMA operands free of
+// bank conflicts: (a) 16 lanes reading the same chunk of 16 consecutive rows, (b) a transposing
+// read where 16 lanes cover 4 consecutive rows x 32 bytes.
+// Tiles are written by global_load_lds_dwordx4: each lane fetches 16 bytes from its own global
+// address and the wavefront's 1 KiB lands at M0 + 16*lane, so no registers are spent on data in
+// flight.  The instruction is issued through inline asm on purpose: the waits are placed by hand
+// (wait_vmcnt) so that loads stay in flight across the compute on the previous tile.
+template <int D>
+__device__ inline int chunk_swizzle(int r) {
+  if (D == 128) return ((r & 3) << 1) | ((r >> 2) & 1) | (r & 8);
+  return (((r >> 1) & 1) << 1) | (((r >> 2) & 1) << 2) | ((r >> 3) & 1);
+}
+
+__device__ inline unsigned lds_offset(const void* p) {
+  return (unsigned)(size_t)(const __attribute__((address_space(3))) char*)p;
+}
+
+__device__ inline void dma16(const void* gptr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_base) : "memory", "m0");
+}
+
+// 4 bytes per lane: the wavefront's 256 bytes land at lds_base + 4*lane
+__device__ inline void dma4(const void* gptr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" : : "v"(gptr), "s"(lds_base) : "memory", "m0");
+}
+
+// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt = imm[3:0] | imm[15:14] << 4; other counters unconstrained)
+template <int N>
+__device__ inline void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// Issue the copy of rows row0 .. row0+63 (rows >= valid repeat the last valid row, their data is
+// always masked by the consumer) of head h into `slot`.  Wavefronts 0 and 1 of the workgroup each
+// issue D/16 loads; other wavefronts issue none.
+template <int D>
+__device__ inline void async_tile_load(bf16* slot, const bf16* src, int64_t row0, int valid, int H, int h, int wave, int lane) {
+  constexpr int C = D / 8;       // 16-byte chunks per row
+  constexpr int RPI = 64 / C;    // rows covered by one wavefront-wide load
+  constexpr int W = 64 / RPI;    // loads per tile
+  if (wave >= 2) return;
+  const int rl = lane / C, pc = lane % C;
+  const unsigned base = lds_offset(slot);
+#pragma unroll
+  for (int a = 0; a < W / 2; ++a) {
+    const int k = wave + 2 * a;
+    const int r = k * RPI + rl;
+    const int c = pc ^ chunk_swizzle<D>(r);
+    const bf16* g = src + ((row0 + min(r, valid - 1)) * H + h) * D + 8 * c;
+    dma16(g, base + k * 1024);
+  }
+}
+template <int D>
+constexpr int loads_per_tile() { return D / 16; }
+
+// 8 consecutive elements (chunk c) of row r
+template <int D>
+__device__ inline bf16x8 lds_row8(const bf16* slot, int r, int c) {
+  return *(const bf16x8*)(slot + r * D + 8 * (c ^ chunk_swizzle<D>(r)));
+}
+
+// Transposing read (ds_read_b64_tr_b16): within each group of 16 lanes, lane x supplies the address
+// of 4 consecutive elements of row r0 + x/4 starting at column dbase + 4*(x%4), and receives the 4
+// elements of column dbase + x from rows r0 .. r0+3.
+template <int D>
+__device__ inline bf16x4 lds_tr4(const bf16* slot, int r0, int dbase, int lane16) {
+  const int r = r0 + (lane16 >> 2), d = dbase + 4 * (lane16 & 3);
+  const bf16* p = slot + r * D + 8 * ((d >> 3) ^ chunk_swizzle<D>(r)) + (d & 7);
+  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)p);
+}
+
+// A/B operand whose 8 contraction slots are rows 16*kk + 8*(e/4) + 4*hf + e%4 of the tile and whose
+// MFMA row/column is tile column 32*dt + lane%32.
+template <int D>
+__device__ inline bf16x8 lds_tr_operand(const bf16* slot, int kk, int dt, int lane) {
+  const int hf = lane >> 5, lane16 = lane & 15, dbase = 32 * dt + 16 * ((lane >> 4) & 1);
+  bf16x4 lo = lds_tr4<D>(slot, 16 * kk + 4 * hf, dbase, lane16);
+  bf16x4 hi = lds_tr4<D>(slot, 16 * kk + 8 + 4 * hf, dbase, lane16);
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 struct BusyTimer {

@@ -1,25 +1,26 @@
 // Block-sparse attention forward (paper Eq. 2) on bf16 MFMA with fp32 online softmax.
 //
 // One workgroup per work item (sequence s, selection head hs, query block i), taken from the
-// longest-first work list.  The item's 64 query rows (times the G query heads of the KV group in
-// per-KV-group mode) are split into strips of 32 rows, one wavefront per strip.  For every selected
-// key block the workgroup stages the K tile (row-major) and the V tile (transposed) in LDS once;
-// each wavefront then computes S^T = K Q^T, keeps the running max / sum per query in registers
-// (a query is a C-matrix column, i.e. one lane pair), and accumulates O^T += V^T P^T.
+// longest-first work list.  The item's 64 query rows (times up to 4 query heads of the KV group in
+// per-KV-group mode) are split into strips of 32 rows, one wavefront per strip.  The K and V tiles
+// of the selected key blocks stream through three LDS slots as a sequence of half-tiles
+// K0 V0 K1 V1 ...: while half-tile n is consumed, n+1 is landing and n+2 is issued, all by
+// asynchronous global->LDS loads that occupy no registers.  Each wavefront computes S^T = K Q^T,
+// keeps the running max / sum per query in registers (a query is a C-matrix column, i.e. one lane
+// pair), and accumulates O^T += V^T P^T, reading V^T straight out of the row-major V tile with the
+// transposing LDS read.
 #include "sb_attn_common.h"
 
 namespace sb {
 
 template <int D, bool OUT_F32, int MAXT>
-__global__ __launch_bounds__(MAXT) void attn_fwd_kernel(AttnParams P) {
-  constexpr int KLD = D + 8;   // K tile row length (elements): 16 B pad keeps 16-lane b128 reads conflict-free
-  constexpr int VLD = 64 + 8;  // V^T tile row length
-  __shared__ __attribute__((aligned(16))) bf16 Ks[64 * KLD];
-  __shared__ __attribute__((aligned(16))) bf16 Vt[D * VLD];
+__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void attn_fwd_kernel(AttnParams P) {
+  __shared__ __attribute__((aligned(1024))) bf16 slots[3][64 * D];
+  constexpr int LPT = loads_per_tile<D>();
   BusyTimer timer;
   timer.start(P);
   const int tid = threadIdx.x, nthr = blockDim.x;
-  const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
   const int64_t row = P.work[blockIdx.x];
   const int hs = (int)(row / P.NQB);
   const int qb = (int)(row - (int64_t)hs * P.NQB);
@@ -36,38 +37,56 @@ __global__ __launch_bounds__(MAXT) void attn_fwd_kernel(AttnParams P) {
   const bool qvalid = head_ok && i * 64 + qloc < L;
   const int64_t tq = seq0 + i * 64 + qloc;
 
+  const int e0 = P.rowptr[row], ntiles = P.rowptr[row + 1] - e0;
+  // The row's block indices are staged in LDS, kJ at a time: reading them from LDS keeps them off
+  // the vector-memory counter that the in-flight tile loads are tracked with.
+  constexpr int kJ = 256;
+  __shared__ int jbuf[kJ];
+  auto stage_indices = [&](int t0) {  // entries t0 .. t0+kJ-1 of the row; all waves call it together
+    __syncthreads();
+    for (int a = tid; a < kJ; a += nthr) jbuf[a] = t0 + a < ntiles ? P.idx[e0 + t0 + a] : 0;
+    __syncthreads();
+  };
+  // half-tile n: K (n even) or V (n odd) of tile n/2, staged in slot n % 3
+  auto issue = [&](int n) {
+    const int j = jbuf[(n >> 1) % kJ];
+    async_tile_load<D>(slots[n % 3], (n & 1) ? P.v : P.k, seq0 + (int64_t)j * 64, min(64, L - j * 64), P.Hkv, g, wave, lane);
+  };
   bf16x8 qf[D / 16];
   {
     const bf16* qp = P.q + (tq * P.Hq + h) * D + 8 * hf;
 #pragma unroll
     for (int ks = 0; ks < D / 16; ++ks) qf[ks] = qvalid ? *(const bf16x8*)(qp + 16 * ks) : zero_bf16x8();
   }
+  stage_indices(0);
+  // the query fragments must have landed before the tile loads start: from here on the only
+  // vector-memory operations in flight are tile loads, which the loop waits for by count
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) asm volatile("" : "+v"(qf[ks]));
+  issue(0);
+  issue(1);
+
   f32x16 oacc[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt) oacc[dt] = zero16();
   float m = -__builtin_inff(), l = 0.f;
 
-  const int e0 = P.rowptr[row], e1 = P.rowptr[row + 1];
-  for (int e = e0; e < e1; ++e) {
-    const int j = P.idx[e];
-    const int64_t kv0 = seq0 + (int64_t)j * 64;
-    const int kvalid = min(64, L - j * 64);
-    __syncthreads();  // every wavefront is done with the previous tile
-    load_tile_rowmajor<D, KLD>(Ks, P.k, kv0, kvalid, P.Hkv, g, tid, nthr);
-    load_tile_transposed<D, KLD, VLD>(Vt, nullptr, P.v, kv0, kvalid, P.Hkv, g, tid, nthr);
-    __syncthreads();
-
+  for (int t = 0; t < ntiles; ++t) {
+    const bool more = t + 1 < ntiles;
+    if (more && (t + 1) % kJ == 0) stage_indices(t + 1);  // drains the loads in flight once per kJ tiles
+    // ---- K half-tile: loads of V_t may stay in flight
+    wait_vmcnt<LPT>();
+    __builtin_amdgcn_s_barrier();
+    if (more) issue(2 * t + 2);
+    const bf16* Ks = slots[(2 * t) % 3];
     f32x16 sacc[2];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
       sacc[mt] = zero16();
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) {
-        bf16x8 a = *(const bf16x8*)(Ks + (32 * mt + l32) * KLD + 16 * ks + 8 * hf);
-        sacc[mt] = mfma32(a, qf[ks], sacc[mt]);
-      }
+      for (int ks = 0; ks < D / 16; ++ks) sacc[mt] = mfma32(lds_row8<D>(Ks, 32 * mt + l32, 2 * ks + hf), qf[ks], sacc[mt]);
     }
-    const bool diag = j == i;
+    const bool diag = t == ntiles - 1;  // the diagonal block is the last entry of every row
     float mx = -__builtin_inff();
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
@@ -94,15 +113,18 @@ __global__ __launch_bounds__(MAXT) void attn_fwd_kernel(AttnParams P) {
     l = l * alpha + rs;
     m = m_new;
 #pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt) {
+    for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
       for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+    // ---- V half-tile: loads of K_{t+1} may stay in flight
+    if (more) wait_vmcnt<LPT>(); else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    if (more) issue(2 * t + 3);
+    const bf16* Vs = slots[(2 * t + 1) % 3];
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        bf16x8 a = *(const bf16x8*)(Vt + (32 * dt + l32) * VLD + 16 * kk + 8 * hf);
-        oacc[dt] = mfma32(a, pb[kk], oacc[dt]);
-      }
-    }
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) oacc[dt] = mfma32(lds_tr_operand<D>(Vs, kk, dt, lane), pb[kk], oacc[dt]);
   }
 
   l += __shfl_xor(l, 32, 64);
