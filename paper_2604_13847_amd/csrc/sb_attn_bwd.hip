@@ -74,12 +74,14 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(MAXT >= 25
     for (int a = tid; a < kJ; a += nthr) jbuf[a] = t0 + a < ntiles ? P.idx[e0 + t0 + a] : 0;
     __syncthreads();
   };
+  TileLoader<D> loader;
+  loader.init(P.Hkv, wave, lane);
   auto issue = [&](int t) {
-    const int j = jbuf[t % kJ];
+    const int j = __builtin_amdgcn_readfirstlane(jbuf[t % kJ]);
     const int64_t kv0 = seq0 + (int64_t)j * 64;
     const int kvalid = min(64, L - j * 64);
-    async_tile_load<D>(tiles[t & 1][0], P.k, kv0, kvalid, P.Hkv, g, wave, lane);
-    async_tile_load<D>(tiles[t & 1][1], P.v, kv0, kvalid, P.Hkv, g, wave, lane);
+    loader.issue(tiles[t & 1][0], P.k, kv0, kvalid, P.Hkv, g);
+    loader.issue(tiles[t & 1][1], P.v, kv0, kvalid, P.Hkv, g);
   };
 
   bf16x8 qf[D / 16], dof[D / 16];
@@ -125,10 +127,14 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(MAXT >= 25
       for (int ks = 0; ks < D / 16; ++ks) sacc = mfma32(lds_row8<D>(Ks, 32 * mt + l32, 2 * ks + hf), qf[ks], sacc);
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) dpacc = mfma32(lds_row8<D>(Vs, 32 * mt + l32, 2 * ks + hf), dof[ks], dpacc);
+      if (diag) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (32 * mt + c_row(v, hf) > qloc) sacc[v] = -__builtin_inff();
+      }
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        float pv = fast_exp2(sacc[v] * P.scale_log2e - lse2);
-        if (diag && 32 * mt + c_row(v, hf) > qloc) pv = 0.f;
+        float pv = fast_exp2(__builtin_fmaf(sacc[v], P.scale_log2e, -lse2));
         dsb[2 * mt + (v >> 3)][v & 7] = (bf16)(pv * (dpacc[v] - dr));
       }
     }
@@ -204,11 +210,13 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(AttnParams P) {
   const int nsel = P.mode == SB_SELECT_PER_QHEAD ? P.G : 1;   // bitmap columns to walk
   const int hpe = P.mode == SB_SELECT_PER_QHEAD ? 1 : P.G;    // query heads per set bit
 
+  TileLoader<D> loader;
+  loader.init(P.Hq, wave, lane);
   auto issue = [&](int buf, int i, int h) {
     const int64_t q0 = seq0 + (int64_t)i * 64;
     const int qv = min(64, L - i * 64);
-    async_tile_load<D>(tiles[buf][0], P.q, q0, qv, P.Hq, h, wave, lane);
-    async_tile_load<D>(tiles[buf][1], P.d_o, q0, qv, P.Hq, h, wave, lane);
+    loader.issue(tiles[buf][0], P.q, q0, qv, P.Hq, h);
+    loader.issue(tiles[buf][1], P.d_o, q0, qv, P.Hq, h);
     // 64 LSE and 64 Dr values: one 4-byte load per lane, wavefront 0 takes LSE and wavefront 1 Dr
     const float* src = (wave == 0 ? P.lse : P.drow) + (int64_t)h * P.T + q0 + min(lane, qv - 1);
     dma4(src, lds_offset(rowstat[buf][wave]));
@@ -275,11 +283,15 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(AttnParams P) {
           const float4 dd = *(const float4*)(dr_s + qr);
           const float lsv[4] = {ls.x, ls.y, ls.z, ls.w};
           const float ddv[4] = {dd.x, dd.y, dd.z, dd.w};
+          if (diag || qv < 64) {  // causal mask inside the diagonal block, rows past the sequence end
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+              if ((diag && kloc > qr + c) || qr + c >= qv) sacc[4 * vg + c] = -__builtin_inff();
+          }
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             const int v = 4 * vg + c;
-            float pv = fast_exp2(sacc[v] * P.scale_log2e - lsv[c] * 1.4426950408889634f);
-            if ((diag && kloc > qr + c) || qr + c >= qv) pv = 0.f;
+            float pv = fast_exp2(__builtin_fmaf(sacc[v], P.scale_log2e, -lsv[c] * 1.4426950408889634f));
             pa[2 * qt + (v >> 3)][v & 7] = (bf16)pv;
             dsa[2 * qt + (v >> 3)][v & 7] = (bf16)(pv * (dpacc[v] - ddv[c]));
           }

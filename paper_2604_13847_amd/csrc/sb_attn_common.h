@@ -119,8 +119,12 @@ __device__ inline void load_tile_transposed(bf16* dst_t, bf16* dst_rm, const bf1
 // (wait_vmcnt) so that loads stay in flight across the compute on the previous tile.
 template <int D>
 __device__ inline int chunk_swizzle(int r) {
-  if (D == 128) return ((r & 3) << 1) | ((r >> 2) & 1) | (r & 8);
-  return (((r >> 1) & 1) << 1) | (((r >> 2) & 1) << 2) | ((r >> 3) & 1);
+  // D = 128 (16 chunks, one row = all 64 banks): the two low row bits pick the 64-byte quarter of the
+  // row, the next two the chunk inside it.  A transposing read (32 lanes = 4 rows x 64 bytes) then
+  // covers 8 distinct 32-byte bank groups and a row-wise read (16 rows, same chunk) 16 distinct chunks.
+  if (D == 128) return ((r & 3) << 2) | ((r >> 2) & 3);
+  // D = 64 (8 chunks, two rows = all banks): row bit 0 already selects the bank half.
+  return (((r >> 1) & 1) << 2) | ((r >> 2) & 3);
 }
 
 __device__ inline unsigned lds_offset(const void* p) {
@@ -142,26 +146,53 @@ __device__ inline void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-// Issue the copy of rows row0 .. row0+63 (rows >= valid repeat the last valid row, their data is
-// always masked by the consumer) of head h into `slot`.  Wavefronts 0 and 1 of the workgroup each
-// issue D/16 loads; other wavefronts issue none.
+// Per-lane byte offsets (from the tile's first row, head h) of the D/16 loads a loader wavefront
+// issues for a tile: load a covers tile rows (wave + 2a)*RPI .. +RPI-1.  They depend only on the
+// lane and on the tensor's row pitch, so they are computed once per kernel.
 template <int D>
-__device__ inline void async_tile_load(bf16* slot, const bf16* src, int64_t row0, int valid, int H, int h, int wave, int lane) {
-  constexpr int C = D / 8;       // 16-byte chunks per row
-  constexpr int RPI = 64 / C;    // rows covered by one wavefront-wide load
-  constexpr int W = 64 / RPI;    // loads per tile
-  if (wave >= 2) return;
-  const int rl = lane / C, pc = lane % C;
-  const unsigned base = lds_offset(slot);
+struct TileLoader {
+  static constexpr int C = D / 8;      // 16-byte chunks per row
+  static constexpr int RPI = 64 / C;   // rows covered by one wavefront-wide load
+  static constexpr int LPT = D / 16;   // loads per loader wavefront per tile
+  unsigned voff[LPT];
+  int row[LPT], chunk_bytes[LPT];
+  int wave;
+  __device__ inline void init(int H, int wave_, int lane) {
+    wave = wave_;
+    const int rl = lane / C, pc = lane % C;
 #pragma unroll
-  for (int a = 0; a < W / 2; ++a) {
-    const int k = wave + 2 * a;
-    const int r = k * RPI + rl;
-    const int c = pc ^ chunk_swizzle<D>(r);
-    const bf16* g = src + ((row0 + min(r, valid - 1)) * H + h) * D + 8 * c;
-    dma16(g, base + k * 1024);
+    for (int a = 0; a < LPT; ++a) {
+      const int r = ((wave & 1) + 2 * a) * RPI + rl;
+      row[a] = r;
+      chunk_bytes[a] = 16 * (pc ^ chunk_swizzle<D>(r));
+      voff[a] = (unsigned)(r * H * D * 2 + chunk_bytes[a]);
+    }
   }
-}
+  // Issue the copy of rows row0 .. row0+63 (head h) of `src` into `slot`.  Rows >= valid repeat the
+  // last valid row; their data is always masked by the consumer.  Wavefronts 0 and 1 issue LPT loads
+  // each, the others none.  Full tiles (the common case) use a scalar base address plus the
+  // precomputed lane offsets, so no vector arithmetic is spent per load.
+  __device__ inline void issue(bf16* slot, const bf16* src, int64_t row0, int valid, int H, int h) const {
+    if (wave >= 2) return;
+    const unsigned base = lds_offset(slot);
+    const char* tile = (const char*)(src + (row0 * H + h) * D);
+    if (valid >= 64) {
+      const unsigned long long tv = (unsigned long long)tile;  // wave-uniform: move it to scalar registers
+      // (readfirstlane returns int: go through unsigned so that the low half is not sign-extended)
+      const unsigned t_hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(tv >> 32));
+      const unsigned t_lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(tv & 0xffffffffull));
+      const unsigned long long ts = ((unsigned long long)t_hi << 32) | (unsigned long long)t_lo;
+#pragma unroll
+      for (int a = 0; a < LPT; ++a)
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %0, %1"
+                     : : "v"(voff[a]), "s"(ts), "s"(base + ((wave & 1) + 2 * a) * 1024) : "memory", "m0");
+    } else {
+#pragma unroll
+      for (int a = 0; a < LPT; ++a)
+        dma16(tile + (int64_t)min(row[a], valid - 1) * H * D * 2 + chunk_bytes[a], base + ((wave & 1) + 2 * a) * 1024);
+    }
+  }
+};
 template <int D>
 constexpr int loads_per_tile() { return D / 16; }
 

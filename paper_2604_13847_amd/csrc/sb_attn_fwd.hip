@@ -48,9 +48,11 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
     __syncthreads();
   };
   // half-tile n: K (n even) or V (n odd) of tile n/2, staged in slot n % 3
+  TileLoader<D> loader;
+  loader.init(P.Hkv, wave, lane);
   auto issue = [&](int n) {
-    const int j = jbuf[(n >> 1) % kJ];
-    async_tile_load<D>(slots[n % 3], (n & 1) ? P.v : P.k, seq0 + (int64_t)j * 64, min(64, L - j * 64), P.Hkv, g, wave, lane);
+    const int j = __builtin_amdgcn_readfirstlane(jbuf[(n >> 1) % kJ]);
+    loader.issue(slots[n % 3], (n & 1) ? P.v : P.k, seq0 + (int64_t)j * 64, min(64, L - j * 64), P.Hkv, g);
   };
   bf16x8 qf[D / 16];
   {
@@ -80,51 +82,73 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
     if (more) issue(2 * t + 2);
     const bf16* Ks = slots[(2 * t) % 3];
     f32x16 sacc[2];
+    {
+      // all 2 x D/16 operand reads are issued before the first MFMA so that LDS latency is paid once
+      bf16x8 ka[2][D / 16];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
-      sacc[mt] = zero16();
+      for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) sacc[mt] = mfma32(lds_row8<D>(Ks, 32 * mt + l32, 2 * ks + hf), qf[ks], sacc[mt]);
+        for (int ks = 0; ks < D / 16; ++ks) ka[mt][ks] = lds_row8<D>(Ks, 32 * mt + l32, 2 * ks + hf);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
+        sacc[mt] = zero16();
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) sacc[mt] = mfma32(ka[mt][ks], qf[ks], sacc[mt]);
+      }
     }
-    const bool diag = t == ntiles - 1;  // the diagonal block is the last entry of every row
+    // online softmax on the raw scores: p = exp2(scale*log2e * (s - m)), m = running max of raw scores
+    if (t == ntiles - 1) {  // the diagonal block is the last entry of every row: causal mask inside it
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (32 * mt + c_row(v, hf) > qloc) sacc[mt][v] = -__builtin_inff();
+    }
     float mx = -__builtin_inff();
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float x = sacc[mt][v] * P.scale_log2e;
-        if (diag && 32 * mt + c_row(v, hf) > qloc) x = -__builtin_inff();
-        sacc[mt][v] = x;
-        mx = fmaxf(mx, x);
-      }
+      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[mt][v]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m, mx);
-    const float alpha = fast_exp2(m - m_new);
+    const float alpha = fast_exp2((m - m_new) * P.scale_log2e);
+    const float neg_m = -m_new * P.scale_log2e;
     float rs = 0.f;
     bf16x8 pb[4];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        float pv = fast_exp2(sacc[mt][v] - m_new);
+        float pv = fast_exp2(__builtin_fmaf(sacc[mt][v], P.scale_log2e, neg_m));
         rs += pv;
         pb[2 * mt + (v >> 3)][v & 7] = (bf16)pv;
       }
     l = l * alpha + rs;
     m = m_new;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {  // rescale only when some row's max moved
 #pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
+      for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+        for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+    }
     // ---- V half-tile: loads of K_{t+1} may stay in flight
     if (more) wait_vmcnt<LPT>(); else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     if (more) issue(2 * t + 3);
     const bf16* Vs = slots[(2 * t + 1) % 3];
+    {
+      bf16x8 va[D / 32][4];
 #pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
+      for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) oacc[dt] = mfma32(lds_tr_operand<D>(Vs, kk, dt, lane), pb[kk], oacc[dt]);
+        for (int kk = 0; kk < 4; ++kk) va[dt][kk] = lds_tr_operand<D>(Vs, kk, dt, lane);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) oacc[dt] = mfma32(va[dt][kk], pb[kk], oacc[dt]);
+    }
   }
 
   l += __shfl_xor(l, 32, 64);
@@ -146,7 +170,7 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
           *(bf16x4*)((bf16*)P.o + obase + d0) = y;
         }
       }
-    if (hf == 0) P.lse[(int64_t)h * P.T + tq] = (m + __builtin_log2f(l)) * 0.69314718055994531f;
+    if (hf == 0) P.lse[(int64_t)h * P.T + tq] = (m * P.scale_log2e + __builtin_log2f(l)) * 0.69314718055994531f;
   }
   timer.stop(P);
 }

@@ -1,5 +1,5 @@
 // Work plan: longest-first ordering of the query-major items, the key-major transpose of the
-// selection as a bitmap, and heaviest-first ordering of the key-major columns.
+// selection as a bitmap, and heaviest-first ordering of the key-major columns (per KV head).
 //
 // Query-major items.  Item (s,hs,i) costs c = min(k_s, i+1) selected tiles.  Because the cost is a
 // closed form of (k_s, n_s, i), the rank of an item in the order (cost descending, then sequence,
@@ -63,15 +63,21 @@ __global__ __launch_bounds__(256) void plan_transpose_kernel(const int32_t* __re
   }
 }
 
-__global__ __launch_bounds__(256) void plan_bwd_hist_kernel(const int32_t* __restrict__ colcost, int64_t ncol, int32_t* __restrict__ bins) {
+// Key-major columns are ordered heaviest first separately for every KV head g, and the Hkv lists
+// are interleaved (position = rank_in_g * Hkv + g).  Neighbouring workgroups of one KV head then
+// walk neighbouring key blocks of one sequence and meet the same Q/dO tiles in the L2 of their XCD
+// at about the same time, while the heaviest-first rule still holds inside each list.
+__global__ __launch_bounds__(256) void plan_bwd_hist_kernel(const int32_t* __restrict__ colcost, int64_t ncol, int64_t NQB,
+                                                            int32_t* __restrict__ bins) {
   const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (c >= ncol) return;
-  atomicAdd(&bins[min(colcost[c], kBwdBins - 1)], 1);
+  atomicAdd(&bins[(c / NQB) * kBwdBins + min(colcost[c], kBwdBins - 1)], 1);
 }
 
-// one workgroup: bins[b] <- number of columns with cost bin > b (start cursor of bin b in heaviest-first order)
-__global__ __launch_bounds__(1024) void plan_bwd_scan_kernel(int32_t* __restrict__ bins) {
+// one workgroup per KV head: bins[b] <- number of its columns with cost bin > b
+__global__ __launch_bounds__(1024) void plan_bwd_scan_kernel(int32_t* __restrict__ bins_all) {
   __shared__ int sh[1024];
+  int32_t* bins = bins_all + (int64_t)blockIdx.x * kBwdBins;
   const int tid = threadIdx.x;
   constexpr int per = kBwdBins / 1024;
   int v[per], sum = 0;
@@ -91,12 +97,13 @@ __global__ __launch_bounds__(1024) void plan_bwd_scan_kernel(int32_t* __restrict
   for (int a = 0; a < per; ++a) { bins[kBwdBins - 1 - (tid * per + a)] = run; run += v[a]; }
 }
 
-__global__ __launch_bounds__(256) void plan_bwd_scatter_kernel(const int32_t* __restrict__ colcost, int64_t ncol, int32_t* __restrict__ bins,
-                                                               int32_t* __restrict__ work_bwd) {
+__global__ __launch_bounds__(256) void plan_bwd_scatter_kernel(const int32_t* __restrict__ colcost, int64_t ncol, int64_t NQB, int Hkv,
+                                                               int32_t* __restrict__ bins, int32_t* __restrict__ work_bwd) {
   const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (c >= ncol) return;
-  const int pos = atomicAdd(&bins[min(colcost[c], kBwdBins - 1)], 1);
-  work_bwd[pos] = (int32_t)c;
+  const int64_t g = c / NQB;
+  const int rank = atomicAdd(&bins[g * kBwdBins + min(colcost[c], kBwdBins - 1)], 1);
+  work_bwd[(int64_t)rank * Hkv + g] = (int32_t)c;
 }
 
 }  // namespace sb
@@ -131,10 +138,10 @@ extern "C" int sb_plan_worklist(const sb_problem* p, const int32_t* sel_rowptr, 
   hipLaunchKernelGGL(plan_transpose_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, sel_rowptr, sel_idx, t.qb_off,
                      t.bm_off, t.qb_seq, g.NQB, g.Hs, g.G, g.mode, bitmap, colcost);
   SB_LAUNCH_CHECK("plan_transpose_kernel");
-  hipLaunchKernelGGL(plan_bwd_hist_kernel, dim3((unsigned)((ncol + 255) / 256)), dim3(256), 0, st, colcost, ncol, bins);
-  hipLaunchKernelGGL(plan_bwd_scan_kernel, dim3(1), dim3(1024), 0, st, bins);
-  hipLaunchKernelGGL(plan_bwd_scatter_kernel, dim3((unsigned)((ncol + 255) / 256)), dim3(256), 0, st, colcost, ncol, bins,
-                     work_bwd);
+  hipLaunchKernelGGL(plan_bwd_hist_kernel, dim3((unsigned)((ncol + 255) / 256)), dim3(256), 0, st, colcost, ncol, g.NQB, bins);
+  hipLaunchKernelGGL(plan_bwd_scan_kernel, dim3((unsigned)g.Hkv), dim3(1024), 0, st, bins);
+  hipLaunchKernelGGL(plan_bwd_scatter_kernel, dim3((unsigned)((ncol + 255) / 256)), dim3(256), 0, st, colcost, ncol, g.NQB,
+                     g.Hkv, bins, work_bwd);
   SB_LAUNCH_CHECK("plan_bwd kernels");
   return SB_OK;
 }

@@ -39,7 +39,9 @@ def test_config2_sampled(mode):
     assert np.array_equal(np.sort(pv["work_fwd"]), np.arange(lay.sel_rows))
     assert np.all(np.diff(np.diff(r.rowptr_h)[pv["work_fwd"]]) <= 0)
     assert np.array_equal(np.sort(pv["work_bwd"]), np.arange(w.Hkv * lay.num_qblocks))
-    assert np.all(np.diff(np.minimum(pv["colcost"][pv["work_bwd"]], 4095)) <= 0)
+    for g in range(w.Hkv):
+        mine = pv["work_bwd"][g::w.Hkv]
+        assert np.all(mine // lay.num_qblocks == g) and np.all(np.diff(np.minimum(pv["colcost"][mine], 4095)) <= 0)
     assert pv["colcost"].sum() == lay.sel_nnz * (1 if mode == 0 else w.Hq // w.Hkv)
     # sampled query rows, spread over sequences, including first/last rows of sequences
     toks = np.concatenate([rng.integers(0, w.T, size=160), w.cu[:-1], w.cu[1:] - 1]).astype(np.int32)

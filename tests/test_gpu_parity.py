@@ -61,7 +61,9 @@ def check_plan(r: Run):
     assert np.array_equal(pv["colcost"], colcost)
     wb = pv["work_bwd"]
     assert np.array_equal(np.sort(wb), np.arange(Hkv * NQB))
-    assert np.all(np.diff(np.minimum(colcost[wb], 4095)) <= 0)               # heaviest first
+    for g in range(Hkv):                                                     # per KV head: its columns, heaviest first
+        mine = wb[g::Hkv]
+        assert np.all(mine // NQB == g) and np.all(np.diff(np.minimum(colcost[mine], 4095)) <= 0)
     assert colcost.sum() == cost.sum() * (1 if r.mode == 0 else G)
 
 
