@@ -19,6 +19,9 @@ sys.path.insert(0, ROOT)
 import numpy as np  # noqa: E402
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
+# HBM bytes per launch of the attention kernels on cfg2 / per_qhead from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
+# (scaled as described in profiles/attn_kernels_cfg2_per_qhead_hbm_traffic.txt); None for other workloads.
+MEASURED_TRAFFIC_BYTES = {("cfg2", "per_qhead"): {"fwd": 1.264e9 + 0.273e9, "bwd_dq": 1.307e9 + 0.268e9, "bwd_dkv": 12.708e9 + 0.135e9}}
 
 
 def make_workload(name, seed):
@@ -162,7 +165,8 @@ def main():
         "attention_only": {"ms": round(attn_ms, 4), "tflops": round(flops_step / (attn_ms * 1e-3) / 1e12, 3)},
         "kernel_ms": {n: round(x, 4) for n, x in kavg.items()},
         "roofline": {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 3), "peak": BF16_MFMA_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 5), "traffic": None,
+                     "unit": "TFLOP/s", "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 5),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.mode), {}).get(dom),
                      "flops_per_launch": dom_flops, "avg_launch_ms": round(kavg[dom], 4)},
     }
 
