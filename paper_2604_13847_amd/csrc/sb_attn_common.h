@@ -19,6 +19,7 @@ struct AttnParams {
   const float* drow;  // [Hq][T] rowsum(dO * O)
   void* dq; void* dk; void* dv;
   const int32_t* rowptr; const int32_t* idx; const int32_t* work;
+  const WorkItem* items;  // descriptors of the query-major items, in work order
   const uint32_t* bitmap;
   const int32_t* cu; const int32_t* qb_off; const int32_t* qb_seq; const int64_t* bm_off;
   int64_t NQB;
@@ -140,10 +141,12 @@ __device__ inline void dma4(const void* gptr, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" : : "v"(gptr), "s"(lds_base) : "memory", "m0");
 }
 
-// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt = imm[3:0] | imm[15:14] << 4; other counters unconstrained)
+// s_waitcnt vmcnt(N) only (the other counters stay unconstrained).  The memory clobber keeps the
+// compiler from moving LDS reads of the awaited tile above the wait.
 template <int N>
 __device__ inline void wait_vmcnt() {
-  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
 // Per-lane byte offsets (from the tile's first row, head h) of the D/16 loads a loader wavefront
@@ -193,6 +196,68 @@ struct TileLoader {
     }
   }
 };
+// One wavefront copies a strip of 32 rows of one head of a [T][H][D] tensor into an LDS slot of its
+// own, with the same swizzled layout as above.  `strip` points at the first row's head slice (it is
+// wave-uniform), `valid` is the number of rows of the strip that exist (<= 0 when the whole strip
+// lies past the end of the sequence): missing rows repeat the sequence's last row, and the consumer
+// masks them.
+// Full strips (the common case) are issued four loads at a time: the instruction's immediate
+// offset moves both the global and the LDS address, so one M0 value serves four consecutive KiB of
+// the slot and the per-lane global offsets are pre-biased by the same amount.  A wavefront issues
+// one instruction per four clocks at best, so every instruction saved here is time the wavefront
+// can spend issuing MFMAs.
+template <int D>
+struct StripLoader {
+  static constexpr int C = D / 8;        // 16-byte chunks per row
+  static constexpr int RPI = 64 / C;     // rows covered by one wavefront-wide load
+  static constexpr int LPS = 32 / RPI;   // loads per strip
+  static_assert(LPS % 4 == 0, "loads are issued in groups of four");
+  unsigned voff[LPS];                    // lane offset of load a, minus 1024 * (a % 4)
+  int row[LPS], chunk_bytes[LPS];
+  int pitch;                             // bytes between consecutive rows
+  __device__ inline void init(int H, int lane) {
+    const int rl = lane / C, pc = lane % C;
+    pitch = H * D * 2;
+#pragma unroll
+    for (int a = 0; a < LPS; ++a) {
+      const int r = a * RPI + rl;
+      row[a] = r;
+      chunk_bytes[a] = 16 * (pc ^ chunk_swizzle<D>(r));
+      // r * pitch >= 1024 * a * H, so the bias never makes the offset negative
+      voff[a] = (unsigned)(r * pitch + chunk_bytes[a] - 1024 * (a & 3));
+    }
+  }
+  // all 32 rows exist; `strip` must be wave-uniform
+  __device__ inline void issue_full(unsigned slot, const char* strip) const {
+    const unsigned long long tv = (unsigned long long)strip;
+    // (readfirstlane returns int: go through unsigned so that the low half is not sign-extended)
+    const unsigned t_hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(tv >> 32));
+    const unsigned t_lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(tv & 0xffffffffull));
+    const unsigned long long ts = ((unsigned long long)t_hi << 32) | (unsigned long long)t_lo;
+    // The base is copied by a scalar instruction first: a scalar register written by a vector
+    // instruction (readfirstlane) must not be read by a vector-memory instruction within 5 wait
+    // states, while scalar reads of it are interlocked.  M0 needs one wait state (s_nop 0) before
+    // the load that uses it.
+#pragma unroll
+    for (int a = 0; a < LPS; a += 4) {
+      unsigned long long base;
+      asm volatile("s_mov_b64 %0, %6\n\ts_mov_b32 m0, %5\n\ts_nop 0\n\t"
+                   "global_load_lds_dwordx4 %1, %0\n\t"
+                   "global_load_lds_dwordx4 %2, %0 offset:1024\n\t"
+                   "global_load_lds_dwordx4 %3, %0 offset:2048\n\t"
+                   "global_load_lds_dwordx4 %4, %0 offset:3072"
+                   : "=&s"(base) : "v"(voff[a]), "v"(voff[a + 1]), "v"(voff[a + 2]), "v"(voff[a + 3]), "s"(slot + a * 1024), "s"(ts) : "memory", "m0");
+    }
+  }
+  __device__ inline void issue(unsigned slot, const char* strip, int valid) const {
+    if (valid >= 32) {
+      issue_full(slot, strip);
+    } else {
+#pragma unroll
+      for (int a = 0; a < LPS; ++a) dma16(strip + (int64_t)min(row[a], valid - 1) * pitch + chunk_bytes[a], slot + a * 1024);
+    }
+  }
+};
 template <int D>
 constexpr int loads_per_tile() { return D / 16; }
 
@@ -220,6 +285,41 @@ __device__ inline bf16x8 lds_tr_operand(const bf16* slot, int kk, int dt, int la
   bf16x4 lo = lds_tr4<D>(slot, 16 * kk + 4 * hf, dbase, lane16);
   bf16x4 hi = lds_tr4<D>(slot, 16 * kk + 8 + 4 * hf, dbase, lane16);
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// x * f for an accumulator element that lives in an accumulation register.  Written as one opaque
+// block so that the copies to and from the arithmetic registers stay inside the (rarely taken)
+// branch that needs them instead of being hoisted into the main loop.
+__device__ inline float scale_acc(float x, float f) {
+  float tmp;
+  asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\tv_accvgpr_write_b32 %0, %1" : "+a"(x), "=&v"(tmp) : "v"(f));
+  return x;
+}
+
+// max(a, b, c) in one instruction.  Written as asm because the compiler's fmax first quiets a possible
+// signalling NaN in every operand it has not produced itself (an extra instruction per value read
+// back from an accumulator); a NaN operand is simply dropped by the hardware instruction.
+__device__ inline float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
+// acc + p[0] + p[1] in one instruction (fp32 accumulation of two bf16 values)
+__device__ inline float sum2(bf16x2 p, float acc) {
+  bf16x2 one;
+  one[0] = (bf16)1.0f;
+  one[1] = (bf16)1.0f;
+  return __builtin_amdgcn_fdot2_f32_bf16(p, one, acc, false);
+}
+
+// max of x over the two lanes l and l + 32 (both receive it): one lane-half swap, no LDS round trip
+__device__ inline float max_across_halves(float x) {
+  const unsigned u = __float_as_uint(x);
+  // returns {own low half | partner's low half, partner's high half | own high half}: element 0 holds
+  // the low half's value in every lane, element 1 the high half's
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

@@ -1,176 +1,343 @@
 // Block-sparse attention forward (paper Eq. 2) on bf16 MFMA with fp32 online softmax.
 //
-// One workgroup per work item (sequence s, selection head hs, query block i), taken from the
-// longest-first work list.  The item's 64 query rows (times up to 4 query heads of the KV group in
-// per-KV-group mode) are split into strips of 32 rows, one wavefront per strip.  The K and V tiles
-// of the selected key blocks stream through three LDS slots as a sequence of half-tiles
-// K0 V0 K1 V1 ...: while half-tile n is consumed, n+1 is landing and n+2 is issued, all by
-// asynchronous global->LDS loads that occupy no registers.  Each wavefront computes S^T = K Q^T,
-// keeps the running max / sum per query in registers (a query is a C-matrix column, i.e. one lane
-// pair), and accumulates O^T += V^T P^T, reading V^T straight out of the row-major V tile with the
-// transposing LDS read.
+// One workgroup of two wavefronts per work item (sequence s, query head, query block i), taken from
+// the longest-first work list.  The two wavefronts split every selected key block by KEYS: wavefront
+// w owns keys 32w .. 32w+31 of each block and all 64 query rows, and runs an online softmax of its
+// own over its half of the keys (running max, running sum and an unnormalised O per wavefront); the
+// two partial results are merged once, at the end, through LDS.  Because a wavefront only ever
+// touches its own key strips, it stages them itself (asynchronous global->LDS loads into a private
+// ring of strips K0 V0 K1 V1 ..., three strips ahead) and the main loop has no barrier at all.
+// Each K / V^T operand read from LDS feeds two MFMAs (one per 32-query half), which halves the LDS
+// traffic per flop compared with a split by query rows.
+// S^T = K Q^T puts a query in a C-matrix column, so the softmax statistics are per lane and the
+// probabilities convert to the B operand of O^T += V^T P^T without any cross-lane movement; V^T is
+// read straight out of the row-major V strip with the transposing LDS read.
+#include <type_traits>
+
 #include "sb_attn_common.h"
 
 namespace sb {
 
-template <int D, bool OUT_F32, int MAXT>
-__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void attn_fwd_kernel(AttnParams P) {
-  __shared__ __attribute__((aligned(1024))) bf16 slots[3][64 * D];
-  constexpr int LPT = loads_per_tile<D>();
+template <int D, bool OUT_F32>
+__global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void attn_fwd_kernel(AttnParams P, int n_items, int heads) {
+  constexpr int NS = 4;          // strips in a wavefront's ring
+  constexpr int SLOT = 32 * D;   // elements per strip
+  constexpr int LPS = StripLoader<D>::LPS;
+  constexpr float kLazy = 8.0f;  // see the softmax below
+  __shared__ __attribute__((aligned(1024))) bf16 ring[2][NS][SLOT];
+  static_assert(sizeof(bf16) * NS * SLOT >= (16 * (D / 32) + 2) * 64 * sizeof(float), "merge buffer must fit in a ring");
   BusyTimer timer;
   timer.start(P);
-  const int tid = threadIdx.x, nthr = blockDim.x;
+  const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-  const int64_t row = P.work[blockIdx.x];
-  const int hs = (int)(row / P.NQB);
-  const int qb = (int)(row - (int64_t)hs * P.NQB);
-  const int s = P.qb_seq[qb];
-  const int i = qb - P.qb_off[s];
-  const int64_t seq0 = P.cu[s];
-  const int L = P.cu[s + 1] - P.cu[s];
-  // per-KV-group mode: a workgroup serves up to 4 query heads of the group, blockIdx.y picks which
-  const int hh = blockIdx.y * (nthr >> 7) + (wave >> 1), strip = wave & 1;
-  const bool head_ok = P.mode == SB_SELECT_PER_QHEAD || hh < P.G;
-  const int h = P.mode == SB_SELECT_PER_QHEAD ? hs : hs * P.G + (head_ok ? hh : 0);
-  const int g = h / P.G;
-  const int qloc = strip * 32 + l32;  // this lane's query row inside the block
-  const bool qvalid = head_ok && i * 64 + qloc < L;
-  const int64_t tq = seq0 + i * 64 + qloc;
+  // Workgroup id -> (position in the work list, query head of the group).  In per-KV-group mode the
+  // `heads` query heads of an item take ids that are 8 apart, so they run on the same XCD (ids are
+  // dealt round-robin to the 8 XCDs) and share its L2 for the K/V strips.
+  const int pos = (int)(blockIdx.x / (8u * heads)) * 8 + (int)(blockIdx.x & 7u);
+  if (pos >= n_items) return;
+  const int hh = (int)(blockIdx.x >> 3) % heads;
+  const WorkItem item = P.items[pos];
+  const int hs = item.hs, i = item.i, L = item.len, e0 = item.e0, ntiles = item.ntiles;
+  const int64_t seq0 = item.seq0;
+  const int h = P.mode == SB_SELECT_PER_QHEAD ? hs : hs * P.G + hh;
+  const int g = P.mode == SB_SELECT_PER_QHEAD ? hs / P.G : hs;
 
-  const int e0 = P.rowptr[row], ntiles = P.rowptr[row + 1] - e0;
-  // The row's block indices are staged in LDS, kJ at a time: reading them from LDS keeps them off
-  // the vector-memory counter that the in-flight tile loads are tracked with.
-  constexpr int kJ = 256;
-  __shared__ int jbuf[kJ];
-  auto stage_indices = [&](int t0) {  // entries t0 .. t0+kJ-1 of the row; all waves call it together
-    __syncthreads();
-    for (int a = tid; a < kJ; a += nthr) jbuf[a] = t0 + a < ntiles ? P.idx[e0 + t0 + a] : 0;
-    __syncthreads();
-  };
-  // half-tile n: K (n even) or V (n odd) of tile n/2, staged in slot n % 3
-  TileLoader<D> loader;
-  loader.init(P.Hkv, wave, lane);
-  auto issue = [&](int n) {
-    const int j = __builtin_amdgcn_readfirstlane(jbuf[(n >> 1) % kJ]);
-    loader.issue(slots[n % 3], (n & 1) ? P.v : P.k, seq0 + (int64_t)j * 64, min(64, L - j * 64), P.Hkv, g);
-  };
-  bf16x8 qf[D / 16];
-  {
-    const bf16* qp = P.q + (tq * P.Hq + h) * D + 8 * hf;
+  // query fragments of both 32-row halves: qf[b][ks] = Q[32b + lane%32][16ks + 8*(lane/32) .. +7]
+  bf16x8 qf[2][D / 16];
+  bool qvalid[2];
+  int64_t tq[2];
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) qf[ks] = qvalid ? *(const bf16x8*)(qp + 16 * ks) : zero_bf16x8();
+  for (int b = 0; b < 2; ++b) {
+    const int qloc = 32 * b + l32;
+    qvalid[b] = i * 64 + qloc < L;
+    tq[b] = seq0 + i * 64 + qloc;
+    const bf16* qp = P.q + (tq[b] * P.Hq + h) * D + 8 * hf;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) qf[b][ks] = qvalid[b] ? *(const bf16x8*)(qp + 16 * ks) : zero_bf16x8();
   }
-  stage_indices(0);
-  // the query fragments must have landed before the tile loads start: from here on the only
-  // vector-memory operations in flight are tile loads, which the loop waits for by count
+  // The row's block indices live in one register across the wavefront (lane a holds entry jb0 + a),
+  // refilled every ~64 tiles; a refill waits for all loads in flight, which is rare enough.  Requests
+  // run at most two entries behind the newest one, so the window keeps two entries of slack.
+  int jb0 = 0;
+  int jreg = lane < ntiles ? P.idx[e0 + lane] : 0;
+  auto refill = [&](int first) __attribute__((always_inline)) {
+    jb0 = first;
+    jreg = jb0 + lane < ntiles ? P.idx[e0 + jb0 + lane] : 0;
+    // wait here, inside the caller's branch: otherwise the compiler puts a full wait at the join after
+    // it, which would drain the strip loads in flight every time
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+  };
+  auto block_of = [&](int x) __attribute__((always_inline)) {
+    if (x - jb0 >= 64) refill(x - 2);
+    return __builtin_amdgcn_readlane(jreg, x - jb0);
+  };
+  // The wavefront's strips (rows 32*wave .. +31 of a selected block's K or V) are loaded in the order
+  // in which the pipelined loop below consumes them:
+  //   c = 0: K_0;   c = 2i+1: K_{i+1};   c = 2i+2: V_i;   c = 2*ntiles-1 (the last): V_{ntiles-1}
+  // Strip c lives in ring slot c % NS and is issued as soon as strip c - NS has been read.
+  StripLoader<D> loader;
+  loader.init(P.Hkv, lane);
+  const int nstrips = 2 * ntiles;
+  const char* const k0 = (const char*)(P.k + ((seq0 + 32 * wave) * P.Hkv + g) * D);  // this wavefront's strip of block 0
+  const char* const v0 = (const char*)(P.v + ((seq0 + 32 * wave) * P.Hkv + g) * D);
+  const unsigned block_pitch = 64u * (unsigned)P.Hkv * D * 2;  // bytes from one key block to the next
+  const unsigned ring0 = lds_offset(&ring[wave][0][0]);
+  const int Lw = L - 32 * wave;  // rows of the sequence from this wavefront's strip of block 0 on
+  auto issue_strip = [&](int slot, bool is_v, int tile) __attribute__((always_inline)) {
+    const int j = block_of(tile);
+    loader.issue(ring0 + slot * (SLOT * 2), (is_v ? v0 : k0) + (unsigned long long)(unsigned)j * block_pitch, Lw - j * 64);
+  };
+  int issued = -1;  // newest strip issued so far
+  auto try_issue = [&](int c) __attribute__((always_inline)) {
+    if (c >= nstrips) return;
+    const bool is_v = c == nstrips - 1 || (c != 0 && (c & 1) == 0);
+    const int tile = c == 0 ? 0 : c == nstrips - 1 ? ntiles - 1 : (c & 1) ? (c + 1) >> 1 : (c >> 1) - 1;
+    issue_strip(c % NS, is_v, tile);
+    issued = c;
+  };
+  // waits until strip c has landed (loads complete in order, so the newer ones may stay in flight)
+  auto wait_strip = [&](int c) __attribute__((always_inline)) {
+    const int younger = issued - c;
+    if (younger >= 3) wait_vmcnt<3 * LPS>();
+    else if (younger == 2) wait_vmcnt<2 * LPS>();
+    else if (younger == 1) wait_vmcnt<LPS>();
+    else wait_vmcnt<0>();
+  };
+  // LDS addresses of this lane's operand reads within slot 0 of the wavefront's ring; the slot is a
+  // compile-time offset wherever the loop is unrolled
+  unsigned k_addr[D / 16], v_addr[D / 32][2];
 #pragma unroll
-  for (int ks = 0; ks < D / 16; ++ks) asm volatile("" : "+v"(qf[ks]));
-  issue(0);
-  issue(1);
-
-  f32x16 oacc[D / 32];
+  for (int ks = 0; ks < D / 16; ++ks) k_addr[ks] = ring0 + l32 * (D * 2) + 16 * ((2 * ks + hf) ^ chunk_swizzle<D>(l32));
 #pragma unroll
-  for (int dt = 0; dt < D / 32; ++dt) oacc[dt] = zero16();
-  float m = -__builtin_inff(), l = 0.f;
-
-  for (int t = 0; t < ntiles; ++t) {
-    const bool more = t + 1 < ntiles;
-    if (more && (t + 1) % kJ == 0) stage_indices(t + 1);  // drains the loads in flight once per kJ tiles
-    // ---- K half-tile: loads of V_t may stay in flight
-    wait_vmcnt<LPT>();
-    __builtin_amdgcn_s_barrier();
-    if (more) issue(2 * t + 2);
-    const bf16* Ks = slots[(2 * t) % 3];
-    f32x16 sacc[2];
-    {
-      // all 2 x D/16 operand reads are issued before the first MFMA so that LDS latency is paid once
-      bf16x8 ka[2][D / 16];
+  for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) ka[mt][ks] = lds_row8<D>(Ks, 32 * mt + l32, 2 * ks + hf);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        sacc[mt] = zero16();
-#pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) sacc[mt] = mfma32(ka[mt][ks], qf[ks], sacc[mt]);
-      }
+    for (int half = 0; half < 2; ++half) {
+      const int r = 8 * half + 4 * hf + ((lane & 15) >> 2), d = 32 * dt + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+      v_addr[dt][half] = ring0 + r * (D * 2) + 16 * ((d >> 3) ^ chunk_swizzle<D>(r)) + 2 * (d & 7);
     }
-    // online softmax on the raw scores: p = exp2(scale*log2e * (s - m)), m = running max of raw scores
-    if (t == ntiles - 1) {  // the diagonal block is the last entry of every row: causal mask inside it
+  bf16x8 ka[D / 16], va[D / 32][2];
+  auto read_k = [&](int slot) __attribute__((always_inline)) {  // operands of S^T = K Q^T: K rows of this wavefront, all of d
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          if (32 * mt + c_row(v, hf) > qloc) sacc[mt][v] = -__builtin_inff();
-    }
-    float mx = -__builtin_inff();
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[mt][v]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m, mx);
-    const float alpha = fast_exp2((m - m_new) * P.scale_log2e);
-    const float neg_m = -m_new * P.scale_log2e;
-    float rs = 0.f;
-    bf16x8 pb[4];
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float pv = fast_exp2(__builtin_fmaf(sacc[mt][v], P.scale_log2e, neg_m));
-        rs += pv;
-        pb[2 * mt + (v >> 3)][v & 7] = (bf16)pv;
-      }
-    l = l * alpha + rs;
-    m = m_new;
-    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {  // rescale only when some row's max moved
-#pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
-    }
-    // ---- V half-tile: loads of K_{t+1} may stay in flight
-    if (more) wait_vmcnt<LPT>(); else wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();
-    if (more) issue(2 * t + 3);
-    const bf16* Vs = slots[(2 * t + 1) % 3];
-    {
-      bf16x8 va[D / 32][4];
-#pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) va[dt][kk] = lds_tr_operand<D>(Vs, kk, dt, lane);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) oacc[dt] = mfma32(va[dt][kk], pb[kk], oacc[dt]);
-    }
-  }
-
-  l += __shfl_xor(l, 32, 64);
-  const float inv = 1.0f / l;
-  if (qvalid) {
-    const int64_t obase = (tq * P.Hq + h) * D;
+    for (int ks = 0; ks < D / 16; ++ks) ka[ks] = *(const bf16x8 __attribute__((address_space(3)))*)(k_addr[ks] + slot * (SLOT * 2));
+  };
+  // operands of O^T += V^T P^T through the transposing read: contraction slots of step kk are the
+  // keys 16kk + 8*(e/4) + 4*(lane/32) + e%4 (rows 16 apart share the swizzle, so kk is a plain offset)
+  auto read_v = [&](int slot) __attribute__((always_inline)) {
 #pragma unroll
     for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-      for (int vg = 0; vg < 4; ++vg) {
-        const int d0 = 32 * dt + 8 * vg + 4 * hf;
-        float x0 = oacc[dt][4 * vg] * inv, x1 = oacc[dt][4 * vg + 1] * inv, x2 = oacc[dt][4 * vg + 2] * inv,
-              x3 = oacc[dt][4 * vg + 3] * inv;
-        if (OUT_F32) {
-          *(float4*)((float*)P.o + obase + d0) = make_float4(x0, x1, x2, x3);
-        } else {
-          bf16x4 y;
-          y[0] = (bf16)x0; y[1] = (bf16)x1; y[2] = (bf16)x2; y[3] = (bf16)x3;
-          *(bf16x4*)((bf16*)P.o + obase + d0) = y;
-        }
+      for (int kk = 0; kk < 2; ++kk) {
+        bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(v_addr[dt][0] + slot * (SLOT * 2) + kk * 16 * (D * 2)));
+        bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(v_addr[dt][1] + slot * (SLOT * 2) + kk * 16 * (D * 2)));
+        va[dt][kk] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       }
-    if (hf == 0) P.lse[(int64_t)h * P.T + tq] = (m * P.scale_log2e + __builtin_log2f(l)) * 0.69314718055994531f;
+  };
+  // the query fragments and indices must have landed before the strip loads start: from here on the
+  // only vector-memory operations in flight are strip loads, which the loop waits for by count
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) asm volatile("" : "+v"(qf[b][ks]));
+  asm volatile("" : "+v"(jreg));
+
+  f32x16 oacc[D / 32][2];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt) oacc[dt][0] = oacc[dt][1] = zero16();
+  float m[2] = {-__builtin_inff(), -__builtin_inff()}, l[2] = {0.f, 0.f};
+  f32x16 sa[2][2];  // raw scores of the current and the next tile (ping-pong)
+  bf16x8 pb[2][2];
+  float alpha[2];
+
+  auto scores = [&](f32x16* dst) __attribute__((always_inline)) {  // dst = K Q^T for the strip whose operands are in ka
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      dst[b] = zero16();
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks) dst[b] = mfma32(ka[ks], qf[b][ks], dst[b]);
+    }
+  };
+  // online softmax on raw scores sc: p = exp2(scale*log2e * (s - m)) -> pb, running sums updated
+  auto softmax = [&](const f32x16* sc) __attribute__((always_inline)) {
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      float mx = max3(sc[b][0], sc[b][1], sc[b][2]);
+#pragma unroll
+      for (int v = 3; v < 15; v += 2) mx = max3(mx, sc[b][v], sc[b][v + 1]);
+      mx = max_across_halves(fmaxf(mx, sc[b][15]));
+      // Lazy running maximum: the reference m[b] used in the exponent follows the true maximum only
+      // when that has grown by more than kLazy (in log2 units), so p stays below 2^kLazy and the
+      // accumulated O needs rescaling only then.  The result is the same up to rounding (O and the
+      // row sum carry the same factor), and the rescale branch becomes rare instead of the rule.
+      const bool first = m[b] == -__builtin_inff();  // nothing accumulated yet for this query: nothing to rescale
+      const bool move = first | ((mx - m[b]) * P.scale_log2e > kLazy);
+      const float m_new = move ? fmaxf(m[b], mx) : m[b];
+      // a wavefront may have seen no unmasked key yet for a query (its strip of the diagonal block can
+      // be entirely above the diagonal): keep the exponent finite then
+      const float m_use = m_new == -__builtin_inff() ? 0.f : m_new;
+      alpha[b] = first ? 1.0f : fast_exp2((m[b] - m_use) * P.scale_log2e);
+      const float neg_m = -m_use * P.scale_log2e;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) pb[b][v >> 3][v & 7] = (bf16)fast_exp2(__builtin_fmaf(sc[b][v], P.scale_log2e, neg_m));
+      // the row sum adds up the probabilities as rounded to bf16, i.e. exactly the weights the
+      // accumulation below applies, two per instruction
+      float rs = l[b] * alpha[b];
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk)
+      {
+        const bf16x8 x = pb[b][kk];
+        rs = sum2(__builtin_shufflevector(x, x, 0, 1), rs);
+        rs = sum2(__builtin_shufflevector(x, x, 2, 3), rs);
+        rs = sum2(__builtin_shufflevector(x, x, 4, 5), rs);
+        rs = sum2(__builtin_shufflevector(x, x, 6, 7), rs);
+      }
+      l[b] = rs;
+      m[b] = m_new;
+    }
+  };
+  auto rescale = [&]() __attribute__((always_inline)) {
+    if (__builtin_amdgcn_ballot_w64((alpha[0] != 1.0f) | (alpha[1] != 1.0f)) != 0) {
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) oacc[dt][b][v] = scale_acc(oacc[dt][b][v], alpha[b]);
+    }
+  };
+  auto accumulate = [&]() __attribute__((always_inline)) {  // O^T += V^T P^T with the operands in va and pb
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) oacc[dt][b] = mfma32(va[dt][kk], pb[b][kk], oacc[dt][b]);
+  };
+
+  // ---- prologue: S_0, and the K operands of tile 1
+#pragma unroll
+  for (int c = 0; c < NS; ++c) try_issue(c);
+  wait_strip(0);
+  read_k(0);
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  try_issue(NS);
+  scores(sa[0]);
+  if (ntiles > 1) {
+    wait_strip(1);
+    read_k(1);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    try_issue(NS + 1);
+  }
+  // ---- steady state: step t turns S_t into P_t while the MFMAs of S_{t+1} run, then accumulates
+  // P_t V_t while the operands of S_{t+2} are fetched.  The loop is unrolled by two so that ring
+  // slots and the score ping-pong are compile-time; steps far enough from the end of the row
+  // (STEADY) know how many loads are in flight and that every strip they prefetch exists.
+  auto step = [&](auto par_c, auto steady_c, int t) __attribute__((always_inline)) {
+    constexpr int PAR = decltype(par_c)::value;  // t % 2
+    constexpr bool STEADY = decltype(steady_c)::value;
+    constexpr int SV = (2 * PAR + 2) % NS, SK = (2 * PAR + 3) % NS;  // slots of strips 2t+2 (V_t) and 2t+3 (K_{t+2})
+    if (STEADY) wait_vmcnt<3 * LPS>(); else wait_strip(2 * t + 2);
+    read_v(SV);
+    scores(sa[PAR ^ 1]);
+    softmax(sa[PAR]);
+    // The probabilities of the first 16 keys are pinned above the rescale branch so that their
+    // exponentials overlap the score MFMAs; those of the other 16 may sink below it and overlap the
+    // first half of the accumulation MFMAs.
+    asm volatile("" : "+v"(pb[0][0]), "+v"(pb[1][0]));
+    rescale();
+    if (STEADY) {
+      wait_vmcnt<2 * LPS>();
+      read_k(SK);
+    } else if (t + 2 < ntiles) {
+      wait_strip(2 * t + 3);
+      read_k(SK);
+    }
+    __builtin_amdgcn_sched_barrier(0x47F);  // the LDS reads stay above the MFMAs: they must be done before their slot is refilled below
+    accumulate();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the slots about to be refilled have been read
+    if (STEADY) {  // tiles t+2 and t+4 are not the row's last, so their blocks are complete; the window holds them
+      loader.issue_full(ring0 + SV * (SLOT * 2), v0 + (unsigned long long)(unsigned)__builtin_amdgcn_readlane(jreg, t + 2 - jb0) * block_pitch);
+      loader.issue_full(ring0 + SK * (SLOT * 2), k0 + (unsigned long long)(unsigned)__builtin_amdgcn_readlane(jreg, t + 4 - jb0) * block_pitch);
+      issued = 2 * t + 3 + NS;
+    } else {
+      try_issue(2 * t + 2 + NS);
+      try_issue(2 * t + 3 + NS);
+    }
+  };
+  using std::integral_constant;
+  int t = 0;
+  for (; t + 6 < ntiles; t += 2) {  // both steps prefetch tiles <= t + 5, none of them the row's last (the only one that can be ragged)
+    if (t + 5 - jb0 >= 64) refill(t + 2);
+    step(integral_constant<int, 0>(), integral_constant<bool, true>(), t);
+    step(integral_constant<int, 1>(), integral_constant<bool, true>(), t + 1);
+  }
+  for (; t + 1 < ntiles; t += 2) {
+    step(integral_constant<int, 0>(), integral_constant<bool, false>(), t);
+    if (t + 2 < ntiles) step(integral_constant<int, 1>(), integral_constant<bool, false>(), t + 1);
+  }
+  // ---- last tile: the diagonal block, causal mask inside it
+  if ((ntiles - 1) & 1) {
+    sa[0][0] = sa[1][0];
+    sa[0][1] = sa[1][1];
+  }
+  wait_strip(nstrips - 1);
+  read_v((nstrips - 1) % NS);
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      if (32 * wave + c_row(v, hf) > 32 * b + l32) sa[0][b][v] = -__builtin_inff();
+  softmax(sa[0]);
+  rescale();
+  accumulate();
+
+  // ---- merge the two key halves: wavefront w finalises query half w and hands the other half over
+  l[0] += __shfl_xor(l[0], 32, 64);
+  l[1] += __shfl_xor(l[1], 32, 64);
+  float* xbuf = (float*)&ring[wave][0][0];            // this wavefront's outgoing partial, [register][lane]
+  const float* ybuf = (const float*)&ring[wave ^ 1][0][0];  // the partner's
+  constexpr int NR = 16 * (D / 32);
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    if (b != wave) {
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) xbuf[(16 * dt + v) * 64 + lane] = oacc[dt][b][v];
+      xbuf[NR * 64 + lane] = m[b];
+      xbuf[(NR + 1) * 64 + lane] = l[b];
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    if (b == wave) {
+      const float m2 = ybuf[NR * 64 + lane], l2 = ybuf[(NR + 1) * 64 + lane];
+      const float mt = fmaxf(m[b], m2);  // finite for every existing query: its own key is never masked
+      const float w1 = fast_exp2((m[b] - mt) * P.scale_log2e), w2 = fast_exp2((m2 - mt) * P.scale_log2e);
+      const float lt = l[b] * w1 + l2 * w2;
+      const float inv = 1.0f / lt;
+      const float c1 = w1 * inv, c2 = w2 * inv;
+      if (qvalid[b]) {
+        const int64_t obase = (tq[b] * P.Hq + h) * D;
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+          for (int vg = 0; vg < 4; ++vg) {
+            const int d0 = 32 * dt + 8 * vg + 4 * hf;
+            float x[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[e] = oacc[dt][b][4 * vg + e] * c1 + ybuf[(16 * dt + 4 * vg + e) * 64 + lane] * c2;
+            if (OUT_F32) {
+              *(float4*)((float*)P.o + obase + d0) = make_float4(x[0], x[1], x[2], x[3]);
+            } else {
+              bf16x4 y;
+              y[0] = (bf16)x[0]; y[1] = (bf16)x[1]; y[2] = (bf16)x[2]; y[3] = (bf16)x[3];
+              *(bf16x4*)((bf16*)P.o + obase + d0) = y;
+            }
+          }
+        if (hf == 0) P.lse[(int64_t)h * P.T + tq[b]] = (mt * P.scale_log2e + __builtin_log2f(lt)) * 0.69314718055994531f;
+      }
+    }
   }
   timer.stop(P);
 }
@@ -221,6 +388,7 @@ extern "C" int sb_sparse_attn_fwd(const sb_problem* p, const void* q, const void
   }
   P.o = o; P.lse = lse;
   P.rowptr = sel_rowptr; P.idx = sel_idx; P.work = (const int32_t*)(pb + po.work_fwd);
+  P.items = (const WorkItem*)(pb + po.items);
   P.cu = t.cu; P.qb_off = t.qb_off; P.qb_seq = t.qb_seq; P.bm_off = t.bm_off;
   P.NQB = g.NQB; P.T = g.T; P.Hq = g.Hq; P.Hkv = g.Hkv; P.G = g.G; P.Hs = g.Hs; P.mode = g.mode;
   P.scale = g.softmax_scale; P.scale_log2e = g.softmax_scale * 1.4426950408889634f;
@@ -230,16 +398,13 @@ extern "C" int sb_sparse_attn_fwd(const sb_problem* p, const void* q, const void
     SB_CHECK_HIP(hipMemsetAsync(wb + wo.cu_busy, 0, sizeof(uint64_t) * SB_CU_SLOTS, st));
     P.cu_busy = (unsigned long long*)(wb + wo.cu_busy);
   }
-  const int G = g.mode == SB_SELECT_PER_QHEAD ? 1 : g.G;
-  const int parts = (G + 3) / 4, hpp = (G + parts - 1) / parts;  // query heads per workgroup <= 4
-  dim3 grid((unsigned)(g.Hs * g.NQB), (unsigned)parts), block((unsigned)(128 * hpp));
+  const int heads = g.mode == SB_SELECT_PER_QHEAD ? 1 : g.G;  // query heads that share a work item
+  const int64_t n_items = (int64_t)g.Hs * g.NQB;
+  const int64_t n_wg = (n_items + 7) / 8 * 8 * heads;
+  if (n_wg > 0x7fffffffll) { set_error("too many work items for one launch"); return SB_ERR_INVALID_ARG; }
+  dim3 grid((unsigned)n_wg), block(128);
   KernelTimer kt(K_FWD, st);
-#define SB_FWD_LAUNCH(DD, FF)                                                                         \
-  do {                                                                                                \
-    if (hpp == 1) hipLaunchKernelGGL((attn_fwd_kernel<DD, FF, 128>), grid, block, 0, st, P);          \
-    else if (hpp == 2) hipLaunchKernelGGL((attn_fwd_kernel<DD, FF, 256>), grid, block, 0, st, P);     \
-    else hipLaunchKernelGGL((attn_fwd_kernel<DD, FF, 512>), grid, block, 0, st, P);                   \
-  } while (0)
+#define SB_FWD_LAUNCH(DD, FF) hipLaunchKernelGGL((attn_fwd_kernel<DD, FF>), grid, block, 0, st, P, (int)n_items, heads)
   if (g.D == 128) {
     if (P.out_f32) SB_FWD_LAUNCH(128, true); else SB_FWD_LAUNCH(128, false);
   } else {

@@ -14,6 +14,7 @@ namespace sb {
 typedef __bf16 bf16;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
@@ -86,9 +87,23 @@ struct PlanOffsets {
   size_t work_bwd;   // int32 [Hkv*NQB]  column ids (g*NQB + qb): entry r*Hkv + g is the r-th heaviest column of KV head g
   size_t bins;       // int32 [Hkv*kBwdBins + 1] counting-sort cursors
   size_t bitmap;     // uint32 [Hs * bm_words_unit] transpose bitmap: bit i of column (s,hs,j)
+  size_t items;      // WorkItem [Hs*NQB]  descriptors of the query-major items, in work_fwd order
   size_t bytes;
 };
 constexpr int kBwdBins = 4096;
+// Everything a query-major workgroup needs to know about its item, so that it starts with one
+// 32-byte load instead of a chain of dependent table lookups.
+struct WorkItem {
+  int32_t row;     // hs * NQB + query block (index into sel_rowptr)
+  int32_t seq0;    // first token of the sequence
+  int32_t len;     // tokens in the sequence
+  int32_t i;       // query block inside the sequence
+  int32_t e0;      // first selection entry of the row
+  int32_t ntiles;  // selected blocks of the row
+  int32_t hs;      // selection head
+  int32_t s;       // sequence
+};
+static_assert(sizeof(WorkItem) == 32, "WorkItem is loaded as 8 dwords");
 PlanOffsets plan_offsets(const Geo& g);
 
 struct WsOffsets {

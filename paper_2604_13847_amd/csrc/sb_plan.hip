@@ -16,8 +16,10 @@
 namespace sb {
 
 __global__ __launch_bounds__(256) void plan_fwd_kernel(const int32_t* __restrict__ qb_off, const int32_t* __restrict__ kclamp,
-                                                       const int32_t* __restrict__ qb_seq, int S, int64_t NQB, int Hs,
-                                                       int Hkv, int G, int mode, int32_t* __restrict__ work_fwd) {
+                                                       const int32_t* __restrict__ qb_seq, const int32_t* __restrict__ cu,
+                                                       const int32_t* __restrict__ rowptr, int S, int64_t NQB, int Hs,
+                                                       int Hkv, int G, int mode, int32_t* __restrict__ work_fwd,
+                                                       WorkItem* __restrict__ items) {
   const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;  // row id = hs*NQB + qb
   if (row >= (int64_t)Hs * NQB) return;
   const int hs = (int)(row / NQB);
@@ -37,6 +39,10 @@ __global__ __launch_bounds__(256) void plan_fwd_kernel(const int32_t* __restrict
   if (mode == SB_SELECT_PER_QHEAD) hrank = (hs % G) * Hkv + hs / G; else hrank = hs;
   pos += (c < ks) ? hrank : (int64_t)(i - (ks - 1)) * Hs + hrank;
   work_fwd[pos] = (int32_t)row;
+  WorkItem it;
+  it.row = (int32_t)row; it.seq0 = cu[s]; it.len = cu[s + 1] - cu[s]; it.i = i;
+  it.e0 = rowptr[row]; it.ntiles = rowptr[row + 1] - it.e0; it.hs = hs; it.s = s;
+  items[pos] = it;
 }
 
 // one wavefront per CSR row: set the row's bit in each selected column and count the column weights
@@ -133,7 +139,7 @@ extern "C" int sb_plan_worklist(const sb_problem* p, const int32_t* sel_rowptr, 
   // colcost, work_bwd, bins and bitmap are adjacent: clear colcost, bins and bitmap
   SB_CHECK_HIP(hipMemsetAsync(colcost, 0, po.bytes - po.colcost, st));
   hipLaunchKernelGGL(plan_fwd_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, t.qb_off, t.kclamp, t.qb_seq,
-                     g.S, g.NQB, g.Hs, g.Hkv, g.G, g.mode, work_fwd);
+                     t.cu, sel_rowptr, g.S, g.NQB, g.Hs, g.Hkv, g.G, g.mode, work_fwd, (WorkItem*)(base + po.items));
   SB_LAUNCH_CHECK("plan_fwd_kernel");
   hipLaunchKernelGGL(plan_transpose_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, sel_rowptr, sel_idx, t.qb_off,
                      t.bm_off, t.qb_seq, g.NQB, g.Hs, g.G, g.mode, bitmap, colcost);
