@@ -7,14 +7,18 @@
 //        keeps its K/V strip in registers, walks the query blocks that kept j (transpose bitmap,
 //        ascending) for every query head of the KV group and accumulates in registers; each output
 //        element is written once, in a fixed order, so the result is deterministic.
+#include <type_traits>
+
 #include "sb_attn_common.h"
 
 namespace sb {
 
 // ---------------------------------------------------------------------------------------------
+// Dr = rowsum(dO * O) and the log-sum-exp in base 2 (LSE * log2 e), both [Hq][T]
 template <bool O_F32>
 __global__ __launch_bounds__(256) void bwd_prep_kernel(const void* __restrict__ o, const bf16* __restrict__ d_o, int64_t rows,
-                                                       int T, int Hq, int D, float* __restrict__ drow) {
+                                                       int T, int Hq, int D, const float* __restrict__ lse,
+                                                       float* __restrict__ drow, float* __restrict__ lse2) {
   const int lpr = D / 8;  // lanes per (token, head) row, 8 elements each
   const int64_t r = ((int64_t)blockIdx.x * 256 + threadIdx.x) / lpr;
   const int c = threadIdx.x % lpr;
@@ -36,7 +40,9 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(const void* __restrict__ 
     const int64_t t = r / Hq;
     const int h = (int)(r - t * Hq);
     drow[(int64_t)h * T + t] = acc;
+    lse2[(int64_t)h * T + t] = lse[(int64_t)h * T + t] * 1.4426950408889634f;
   }
+  if (blockIdx.x == 0 && threadIdx.x == 0) lse2[(int64_t)Hq * T] = __builtin_inff();  // read in place of the LSE of rows that do not exist
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -166,16 +172,29 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(MAXT >= 25
 
 // ---------------------------------------------------------------------------------------------
 // Key-major dK/dV kernel: 2 wavefronts, each owns 32 keys of key block (s, g, j) and keeps their
-// K and V rows in registers.  The Q and dO tiles (plus LSE and Dr) of the query blocks that kept j
-// are double-buffered in LDS by asynchronous loads; both are read row-wise (S = Q K^T, dP = dO V^T)
-// and through the transposing LDS read (dV += P^T dO, dK += dS^T Q).
-// The column's query blocks come from the transpose bitmap, staged in LDS 64 words (2048 query
-// blocks) per selection head at a time and walked in ascending order.
+// K and V rows in registers for the whole launch.  The Q and dO tiles (plus the rows' log-sum-exp
+// in base 2 and Dr) of the query blocks that kept j are double-buffered in LDS by asynchronous
+// loads; both are read row-wise (S = Q K^T, dP = dO V^T) and through the transposing LDS read
+// (dV += P^T dO, dK += dS^T Q).
+// A tile is processed as two halves of 32 queries, software-pipelined so that the exponentials of
+// one half run under the matrix instructions of the other:
+//   S,dP(half 0);  S,dP(half 1) | P,dS(half 0);  dV,dK(half 0) | P,dS(half 1);  dV,dK(half 1)
+// Tiles that need a mask (the diagonal block, a ragged last query block) take a separate
+// instantiation of the tile body, so the common path has no per-element selects or branches.
+// The column's tiles are visited query block by query block (ascending), all query heads of the KV
+// group at one query block before the next: concurrent columns of one KV head (same XCD) then ask
+// for the same Q/dO tiles at about the same time and meet them in that XCD's L2.
 template <int D, bool OUT_F32>
-__global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(AttnParams P) {
+__global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void attn_bwd_dkv_kernel(AttnParams P) {
+  constexpr int TILE_B = 64 * D * 2;  // bytes of one Q or dO tile
+  constexpr int BUF_B = 2 * TILE_B;   // bytes of one buffer (Q tile, dO tile)
+  constexpr int ROW_B = D * 2;
   __shared__ __attribute__((aligned(1024))) bf16 tiles[2][2][64 * D];  // [buffer][Q, dO]
-  __shared__ __attribute__((aligned(256))) float rowstat[2][2][64];    // [buffer][LSE, Dr]
-  __shared__ uint32_t bm_s[8][64];
+  __shared__ __attribute__((aligned(256))) float rowstat[2][2][64];    // [buffer][LSE * log2(e), Dr]
+  constexpr int kCW = 16;            // bitmap words (32 query blocks each) handled per chunk
+  __shared__ uint32_t bm_s[8][kCW];  // bitmap words of up to 8 selection heads
+  __shared__ uint16_t tl_s[kCW * 32 * 8];  // the chunk's tiles in processing order
+  __shared__ int ntl_s;
   BusyTimer timer;
   timer.start(P);
   const int tid = threadIdx.x;
@@ -206,107 +225,284 @@ __global__ __launch_bounds__(128) void attn_bwd_dkv_kernel(AttnParams P) {
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt) { dkacc[dt] = zero16(); dvacc[dt] = zero16(); }
 
-  const int words = (n + 31) >> 5;
-  const int nsel = P.mode == SB_SELECT_PER_QHEAD ? P.G : 1;   // bitmap columns to walk
-  const int hpe = P.mode == SB_SELECT_PER_QHEAD ? 1 : P.G;    // query heads per set bit
+  // LDS byte addresses of this lane's operand reads inside the current buffer (everything else is a
+  // compile-time offset: rows 16 apart share the swizzle); they move to the other buffer once per tile
+  unsigned row_a[D / 16], tr_a[D / 32][2];
+  unsigned stat_a = lds_offset(&rowstat[0][0][0]) + 16 * hf;
+  {
+    const unsigned tiles0 = lds_offset(&tiles[0][0][0]);
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) row_a[ks] = tiles0 + l32 * ROW_B + 16 * ((2 * ks + hf) ^ chunk_swizzle<D>(l32));
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int r = 8 * half + 4 * hf + ((lane & 15) >> 2), d = 32 * dt + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+        tr_a[dt][half] = tiles0 + r * ROW_B + 16 * ((d >> 3) ^ chunk_swizzle<D>(r)) + 2 * (d & 7);
+      }
+  }
+  auto lds16 = [](unsigned a) __attribute__((always_inline)) { return *(const bf16x8 __attribute__((address_space(3)))*)a; };
+  auto lds_f4 = [](unsigned a) __attribute__((always_inline)) { return *(const f32x4 __attribute__((address_space(3)))*)a; };
+  constexpr int NOP = D / 16;  // operands (and matrix instructions) per pipeline stage
+  // A operands of S = Q K^T / dP = dO V^T: rows 32qt + lane%32 of the tile at byte offset `off`, all of d
+  auto ld_rows = [&](bf16x8* dst, unsigned off) __attribute__((always_inline)) {
+#pragma unroll
+    for (int ks = 0; ks < NOP; ++ks) dst[ks] = lds16(row_a[ks] + off);
+  };
+  // B operands of dV += P^T dO / dK += dS^T Q for the query steps kk0, kk0+1: contraction slots =
+  // queries 16kk + 8(e/4) + 4hf + e%4, column = d (32dt + lane%32), through the transposing read
+  auto ld_tr = [&](bf16x8* dst, unsigned off, int kk0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt) {
+        const unsigned o = off + (kk0 + q) * 16 * ROW_B;
+        bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(tr_a[dt][0] + o));
+        bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(tr_a[dt][1] + o));
+        dst[q * (D / 32) + dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+  };
 
   TileLoader<D> loader;
   loader.init(P.Hq, wave, lane);
-  auto issue = [&](int buf, int i, int h) {
+  constexpr int kLoadsPerTile = 2 * TileLoader<D>::LPT + 1;  // asynchronous loads one wavefront issues per tile
+  auto issue = [&](int buf, int i, int h) __attribute__((always_inline)) {
     const int64_t q0 = seq0 + (int64_t)i * 64;
     const int qv = min(64, L - i * 64);
     loader.issue(tiles[buf][0], P.q, q0, qv, P.Hq, h);
     loader.issue(tiles[buf][1], P.d_o, q0, qv, P.Hq, h);
     // 64 LSE and 64 Dr values: one 4-byte load per lane, wavefront 0 takes LSE and wavefront 1 Dr
-    const float* src = (wave == 0 ? P.lse : P.drow) + (int64_t)h * P.T + q0 + min(lane, qv - 1);
+    // (rows past the end of the sequence read the +inf stored behind the LSE array: their P becomes 0)
+    const float* src = wave == 0 ? (lane < qv ? P.lse2 + (int64_t)h * P.T + q0 + lane : P.lse2 + (int64_t)P.Hq * P.T)
+                                 : P.drow + (int64_t)h * P.T + q0 + min(lane, qv - 1);
     dma4(src, lds_offset(rowstat[buf][wave]));
   };
 
-  for (int w0 = (j >> 5) & ~63; w0 < words; w0 += 64) {  // chunks of 64 bitmap words
-    const int wn = min(64, words - w0);
-    __syncthreads();
-    for (int a = tid; a < nsel * 64; a += 128) {
-      const int sel = a >> 6, w = a & 63;
-      const int hs = P.mode == SB_SELECT_PER_QHEAD ? g * P.G + sel : g;
-      bm_s[sel][w] = w < wn ? P.bitmap[(int64_t)P.Hs * P.bm_off[s] + ((int64_t)hs * n + j) * words + w0 + w] : 0u;
+  f32x16 sacc[2], dpacc[2];
+  bf16x8 pa[4], dsa[4];
+  bf16x8 opA[NOP], opB[NOP];
+  // causal mask inside the diagonal tile (raw scores of queries 32qt .. 32qt+31)
+  auto mask_diag = [&](int qt) __attribute__((always_inline)) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      if (kloc > 32 * qt + c_row(v, hf)) sacc[qt][v] = -__builtin_inff();
+  };
+  // P = exp2(S c - lse2), dS = P (dP - Dr), both to bf16, for registers 4vg .. 4vg+3 = query rows
+  // 32qt + 8vg + 4hf + (0..3).  The rows' statistics are fetched from LDS one stage ahead (ld_stat)
+  // so that no stage has to wait for them.
+  f32x4 st_ls[2], st_dd[2];
+  auto ld_stat = [&](int slot, int qt, int vg) __attribute__((always_inline)) {
+    st_ls[slot] = lds_f4(stat_a + (32 * qt + 8 * vg) * 4);
+    st_dd[slot] = lds_f4(stat_a + 256 + (32 * qt + 8 * vg) * 4);
+  };
+  auto pointwise = [&](int slot, int qt, int vg) __attribute__((always_inline)) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int v = 4 * vg + c;
+      const float pv = fast_exp2(__builtin_fmaf(sacc[qt][v], P.scale_log2e, -st_ls[slot][c]));
+      pa[2 * qt + (v >> 3)][v & 7] = (bf16)pv;
+      dsa[2 * qt + (v >> 3)][v & 7] = (bf16)(pv * (dpacc[qt][v] - st_dd[slot][c]));
     }
-    __syncthreads();
-#pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) asm volatile("" : "+v"(kf[ks]), "+v"(vf[ks]));
-    // iterator over (query block i, query head h) in the order (selection head, i ascending, head)
-    int it_sel = 0, it_w = -1, it_hb = 0, it_i = 0;
-    uint32_t it_bits = 0;
-    auto next = [&](int& i, int& h) -> bool {
-      if (it_hb > 0 && it_hb < hpe) { i = it_i; h = g * P.G + it_hb; ++it_hb; return true; }
-      while (true) {
-        if (it_bits) {
-          const int b = __builtin_ctz(it_bits);
-          it_bits &= it_bits - 1;
-          it_i = 32 * (w0 + it_w) + b;
-          i = it_i;
-          h = P.mode == SB_SELECT_PER_QHEAD ? g * P.G + it_sel : g * P.G;
-          it_hb = 1;
-          return true;
-        }
-        ++it_w;
-        if (it_w >= wn) { it_w = 0; ++it_sel; }
-        if (it_sel >= nsel) return false;
-        it_bits = __builtin_amdgcn_readfirstlane(bm_s[it_sel][it_w]);
+  };
+#define SB_STAGE_FENCE() __builtin_amdgcn_sched_barrier(0)
+// scheduling groups for one stage: NOP x (1 matrix instruction, nds LDS reads, nvalu vector ALU instructions)
+#define SB_PIPE(nds, nvalu)                                                     \
+  _Pragma("unroll") for (int i_ = 0; i_ < NOP; ++i_) {                          \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                          \
+    if ((nds) > 0) __builtin_amdgcn_sched_group_barrier(0x100, (nds), 0);       \
+    if ((nvalu) > 0) __builtin_amdgcn_sched_group_barrier(0x002, (nvalu), 0);   \
+  }
+
+  const int words = (n + 31) >> 5;
+  const bool per_qhead = P.mode == SB_SELECT_PER_QHEAD;
+  const int nsel = per_qhead ? P.G : 1;      // bitmap columns (selection heads) of this KV head
+  const int hpe = per_qhead ? 1 : P.G;       // query heads each set bit stands for
+  int tt = 0;                                // tiles processed so far: tile tt lives in buffer tt & 1
+  for (int sel0 = 0; sel0 < nsel; sel0 += 8) {                  // selection heads in groups of 8
+    const int ns8 = min(8, nsel - sel0);
+    for (int w0 = (j >> 5) & ~(kCW - 1); w0 < words; w0 += kCW) {  // chunks of kCW bitmap words
+      const int wn = min(kCW, words - w0);
+      // ---- the chunk's tile list: entry = (query block - 32 w0) * 8 + head, ordered by query block, then head
+      __syncthreads();
+      for (int a = tid; a < ns8 * kCW; a += 128) {
+        const int sel = a / kCW, w = a % kCW;
+        const int hs = per_qhead ? g * P.G + sel0 + sel : g;
+        bm_s[sel][w] = w < wn ? P.bitmap[(int64_t)P.Hs * P.bm_off[s] + ((int64_t)hs * n + j) * words + w0 + w] : 0u;
       }
-    };
-    int ci, ch, ni = 0, nh = 0;
-    bool have = next(ci, ch);
-    if (have) issue(0, ci, ch);
-    for (int t = 0; have; ++t) {
-      const bool more = next(ni, nh);
-      wait_vmcnt<0>();
+      __syncthreads();
+      if (tid < 64) {  // lane w counts the tiles of word w, a wavefront scan turns counts into list positions
+        int cnt = 0;
+        if (tid < kCW)
+          for (int sel = 0; sel < ns8; ++sel) cnt += __builtin_popcount(bm_s[sel][tid]) * hpe;
+        int incl = cnt;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+          const int up = __shfl_up(incl, off, 64);
+          if (tid >= off) incl += up;
+        }
+        if (tid == 63) ntl_s = incl;
+        int pos = incl - cnt;
+        if (tid < kCW && cnt > 0) {
+          uint32_t any = 0;
+          for (int sel = 0; sel < ns8; ++sel) any |= bm_s[sel][tid];
+          while (any) {
+            const int b = __builtin_ctz(any);
+            any &= any - 1;
+            if (per_qhead) {
+              for (int sel = 0; sel < ns8; ++sel)
+                if ((bm_s[sel][tid] >> b) & 1u) tl_s[pos++] = (uint16_t)((32 * tid + b) * 8 + sel);
+            } else {
+              for (int hh = 0; hh < hpe; ++hh) tl_s[pos++] = (uint16_t)((32 * tid + b) * 8 + hh);
+            }
+          }
+        }
+      }
+      __syncthreads();
+      const int ntl = __builtin_amdgcn_readfirstlane(ntl_s);
+      if (ntl == 0) continue;
+      // the diagonal tiles (query block j itself) are the first of the list: count them
+      int nd = 0;
+      if (j >= 32 * w0 && j < 32 * (w0 + kCW)) {
+        for (int sel = 0; sel < ns8; ++sel) nd += (int)((bm_s[sel][(j >> 5) - w0] >> (j & 31)) & 1u) * hpe;
+        nd = __builtin_amdgcn_readfirstlane(nd);
+      }
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks) asm volatile("" : "+v"(kf[ks]), "+v"(vf[ks]));
+      auto entry = [&](int t, int& i, int& h) __attribute__((always_inline)) {
+        const int e = __builtin_amdgcn_readfirstlane((int)tl_s[t]);
+        i = 32 * w0 + (e >> 3);
+        h = g * P.G + sel0 + (e & 7);
+      };
+      // ---- prologue: tiles 0 and 1 in flight, the first operands of tile 0 on their way to registers
+      {
+        int i0, h0;
+        entry(0, i0, h0);
+        issue(tt & 1, i0, h0);
+        if (ntl > 1) {
+          entry(1, i0, h0);
+          issue((tt + 1) & 1, i0, h0);
+          wait_vmcnt<kLoadsPerTile>();
+        } else {
+          wait_vmcnt<0>();
+        }
+      }
       __builtin_amdgcn_s_barrier();
-      if (more) issue((t + 1) & 1, ni, nh);
-      const bf16* Qs = tiles[t & 1][0];
-      const bf16* dOs = tiles[t & 1][1];
-      const float* lse_s = rowstat[t & 1][0];
-      const float* dr_s = rowstat[t & 1][1];
-      const int qv = min(64, L - ci * 64);
-      const bool diag = ci == j;
-      bf16x8 pa[4], dsa[4];
+      ld_rows(opA, 0);
+      // ---- one tile per iteration, eight stages of NOP matrix instructions each; the operands of a
+      // stage are fetched from LDS while the previous stage computes, and the pointwise work of one half
+      // tile is spread under the matrix instructions of the next stages.  The instruction mix of every
+      // stage is pinned with scheduling groups: one matrix instruction, then its share of the LDS reads
+      // and of the vector arithmetic.
+      auto run_tiles = [&](auto diag_c, int tb, int te) __attribute__((always_inline)) {
+        constexpr bool DIAG = decltype(diag_c)::value;
+        for (int t = tb; t < te; ++t, ++tt) {
+          const int e2 = t + 2 < ntl ? (int)tl_s[t + 2] : 0;
+          // stage 0: S(queries 0..31)
+          ld_rows(opB, TILE_B);
+          sacc[0] = zero16();
 #pragma unroll
-      for (int qt = 0; qt < 2; ++qt) {
-        f32x16 sacc = zero16(), dpacc = zero16();
+          for (int ks = 0; ks < NOP; ++ks) sacc[0] = mfma32(opA[ks], kf[ks], sacc[0]);
+          SB_PIPE(1, 0);
+          SB_STAGE_FENCE();
+          // stage 1: dP(queries 0..31)
+          ld_rows(opA, 32 * ROW_B);
+          ld_stat(0, 0, 0);
+          ld_stat(1, 0, 1);
+          dpacc[0] = zero16();
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) sacc = mfma32(lds_row8<D>(Qs, 32 * qt + l32, 2 * ks + hf), kf[ks], sacc);
+          for (int ks = 0; ks < NOP; ++ks) dpacc[0] = mfma32(opB[ks], vf[ks], dpacc[0]);
+          SB_PIPE(2, 0);
+          SB_STAGE_FENCE();
+          // stage 2: S(queries 32..63) | first half of the pointwise work of queries 0..31
+          if (DIAG) mask_diag(0);
+          ld_rows(opB, TILE_B + 32 * ROW_B);
+          sacc[1] = zero16();
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) dpacc = mfma32(lds_row8<D>(dOs, 32 * qt + l32, 2 * ks + hf), vf[ks], dpacc);
+          for (int ks = 0; ks < NOP; ++ks) sacc[1] = mfma32(opA[ks], kf[ks], sacc[1]);
+          pointwise(0, 0, 0);
+          pointwise(1, 0, 1);
+          SB_PIPE(1, 8);
+          SB_STAGE_FENCE();
+          ld_stat(0, 0, 2);
+          ld_stat(1, 0, 3);
+          SB_STAGE_FENCE();
+          // stage 3: dP(queries 32..63) | second half
+          ld_tr(opA, TILE_B, 0);
+          dpacc[1] = zero16();
 #pragma unroll
-        for (int vg = 0; vg < 4; ++vg) {
-          const int qr = 32 * qt + 8 * vg + 4 * hf;  // query rows qr..qr+3 are registers 4vg..4vg+3
-          const float4 ls = *(const float4*)(lse_s + qr);
-          const float4 dd = *(const float4*)(dr_s + qr);
-          const float lsv[4] = {ls.x, ls.y, ls.z, ls.w};
-          const float ddv[4] = {dd.x, dd.y, dd.z, dd.w};
-          if (diag || qv < 64) {  // causal mask inside the diagonal block, rows past the sequence end
+          for (int ks = 0; ks < NOP; ++ks) dpacc[1] = mfma32(opB[ks], vf[ks], dpacc[1]);
+          pointwise(0, 0, 2);
+          pointwise(1, 0, 3);
+          SB_PIPE(2, 8);
+          SB_STAGE_FENCE();
+          ld_stat(0, 1, 0);
+          ld_stat(1, 1, 1);
+          SB_STAGE_FENCE();
+          // stage 4: dV += P^T dO over queries 0..31 | first half of the pointwise work of queries 32..63
+          if (DIAG) mask_diag(1);
+          ld_tr(opB, 0, 0);
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-              if ((diag && kloc > qr + c) || qr + c >= qv) sacc[4 * vg + c] = -__builtin_inff();
+          for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int dt = 0; dt < D / 32; ++dt) dvacc[dt] = mfma32(pa[q], opA[q * (D / 32) + dt], dvacc[dt]);
+          pointwise(0, 1, 0);
+          pointwise(1, 1, 1);
+          SB_PIPE(2, 8);
+          SB_STAGE_FENCE();
+          ld_stat(0, 1, 2);
+          ld_stat(1, 1, 3);
+          SB_STAGE_FENCE();
+          // stage 5: dK += dS^T Q over queries 0..31 | second half
+          ld_tr(opA, TILE_B, 2);
+#pragma unroll
+          for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int dt = 0; dt < D / 32; ++dt) dkacc[dt] = mfma32(dsa[q], opB[q * (D / 32) + dt], dkacc[dt]);
+          pointwise(0, 1, 2);
+          pointwise(1, 1, 3);
+          SB_PIPE(2, 8);
+          SB_STAGE_FENCE();
+          // stage 6: dV over queries 32..63
+          ld_tr(opB, 0, 2);
+#pragma unroll
+          for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int dt = 0; dt < D / 32; ++dt) dvacc[dt] = mfma32(pa[2 + q], opA[q * (D / 32) + dt], dvacc[dt]);
+          SB_PIPE(2, 0);
+          SB_STAGE_FENCE();
+          // stage 7: dK over queries 32..63.  Its operands are the last LDS reads of this tile: once they
+          // have arrived the buffer is free, and once the next tile has landed everywhere (barrier) its
+          // first operands can be fetched under this stage's matrix instructions.
+          asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+          __builtin_amdgcn_s_barrier();
+          if (t + 2 < ntl) {
+            const int e = __builtin_amdgcn_readfirstlane(e2);
+            issue(tt & 1, 32 * w0 + (e >> 3), g * P.G + sel0 + (e & 7));
           }
+          {
+            const int dl = (tt & 1) ? -BUF_B : BUF_B, ds = (tt & 1) ? -512 : 512;
 #pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            const int v = 4 * vg + c;
-            float pv = fast_exp2(__builtin_fmaf(sacc[v], P.scale_log2e, -lsv[c] * 1.4426950408889634f));
-            pa[2 * qt + (v >> 3)][v & 7] = (bf16)pv;
-            dsa[2 * qt + (v >> 3)][v & 7] = (bf16)(pv * (dpacc[v] - ddv[c]));
+            for (int ks = 0; ks < D / 16; ++ks) row_a[ks] += dl;
+#pragma unroll
+            for (int dt = 0; dt < D / 32; ++dt) { tr_a[dt][0] += dl; tr_a[dt][1] += dl; }
+            stat_a += ds;
           }
-        }
-      }
+          SB_STAGE_FENCE();
+          ld_rows(opA, 0);  // (after the last tile of the chunk this reads a stale buffer and is not used)
 #pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt)
+          for (int q = 0; q < 2; ++q)
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          dvacc[dt] = mfma32(pa[kk], lds_tr_operand<D>(dOs, kk, dt, lane), dvacc[dt]);
-          dkacc[dt] = mfma32(dsa[kk], lds_tr_operand<D>(Qs, kk, dt, lane), dkacc[dt]);
+            for (int dt = 0; dt < D / 32; ++dt) dkacc[dt] = mfma32(dsa[2 + q], opB[q * (D / 32) + dt], dkacc[dt]);
+          SB_PIPE(1, 0);
+          SB_STAGE_FENCE();
         }
-      have = more; ci = ni; ch = nh;
+      };
+      run_tiles(std::true_type(), 0, nd);
+      run_tiles(std::false_type(), nd, ntl);
     }
   }
+#undef SB_PIPE
+#undef SB_STAGE_FENCE
   // C layout: column = d (32dt + l32), register v = key row c_row(v, hf) of this wavefront's strip
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt)
@@ -388,7 +584,8 @@ extern "C" int sb_sparse_attn_bwd(const sb_problem* p, const void* q, const void
     P.q = (const bf16*)q; P.k = (const bf16*)k; P.v = (const bf16*)v; P.d_o = (const bf16*)d_o;
   }
   float* drow = (float*)(wb + wo.drow);
-  P.lse = (float*)lse; P.drow = drow; P.dq = dq; P.dk = dk; P.dv = dv;
+  float* lse2 = (float*)(wb + wo.lse2);
+  P.lse = (float*)lse; P.drow = drow; P.lse2 = lse2; P.dq = dq; P.dk = dk; P.dv = dv;
   P.rowptr = sel_rowptr; P.idx = sel_idx;
   P.bitmap = (const uint32_t*)(pb + po.bitmap);
   P.cu = t.cu; P.qb_off = t.qb_off; P.qb_seq = t.qb_seq; P.bm_off = t.bm_off;
@@ -405,8 +602,8 @@ extern "C" int sb_sparse_attn_bwd(const sb_problem* p, const void* q, const void
   dim3 pgrid((unsigned)((rows + rows_per_wg - 1) / rows_per_wg));
   {
   KernelTimer kt(K_BWD_PREP, st);
-  if (f32) hipLaunchKernelGGL(bwd_prep_kernel<true>, pgrid, dim3(256), 0, st, o, P.d_o, rows, g.T, g.Hq, g.D, drow);
-  else hipLaunchKernelGGL(bwd_prep_kernel<false>, pgrid, dim3(256), 0, st, o, P.d_o, rows, g.T, g.Hq, g.D, drow);
+  if (f32) hipLaunchKernelGGL(bwd_prep_kernel<true>, pgrid, dim3(256), 0, st, o, P.d_o, rows, g.T, g.Hq, g.D, lse, drow, lse2);
+  else hipLaunchKernelGGL(bwd_prep_kernel<false>, pgrid, dim3(256), 0, st, o, P.d_o, rows, g.T, g.Hq, g.D, lse, drow, lse2);
   }
   SB_LAUNCH_CHECK("bwd_prep_kernel");
 

@@ -17,6 +17,7 @@ struct AttnParams {
   void* o;            // forward output (bf16 or float per out_f32)
   float* lse;         // [Hq][T]
   const float* drow;  // [Hq][T] rowsum(dO * O)
+  const float* lse2;  // [Hq][T] lse * log2(e)
   void* dq; void* dk; void* dv;
   const int32_t* rowptr; const int32_t* idx; const int32_t* work;
   const WorkItem* items;  // descriptors of the query-major items, in work order

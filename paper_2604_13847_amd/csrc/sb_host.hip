@@ -148,6 +148,7 @@ static WsOffsets ws_offsets(const Geo& g, bool bwd) {
   w.oc = o;  o = align_up(o + 0);
   w.doc = o; o = align_up(o + (bwd ? qbytes : 0));
   w.drow = o; o = align_up(o + (bwd ? sizeof(float) * (size_t)g.T * g.Hq : 0));
+  w.lse2 = o; o = align_up(o + (bwd ? sizeof(float) * ((size_t)g.T * g.Hq + 1) : 0));  // + one +inf sentinel
   w.bytes = o;
   return w;
 }

@@ -110,6 +110,7 @@ struct WsOffsets {
   size_t cu_busy;    // uint64 [SB_CU_SLOTS]
   size_t qc, kc, vc, oc, doc;  // bf16 copies when dtype == SB_F32 (0 size otherwise)
   size_t drow;       // float [Hq][T]
+  size_t lse2;       // float [Hq][T]
   size_t bytes;
 };
 WsOffsets fwd_ws_offsets(const Geo& g);
