@@ -46,34 +46,40 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(const void* __restrict__ 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Query-major dQ kernel.  Same work items and strips as the forward.  The K and V tiles of the
-// selected blocks are double-buffered in LDS as whole tiles: while tile t is consumed, tile t+1 is
-// in flight (asynchronous global->LDS loads).  K is read row-wise for S^T = K Q^T and through the
-// transposing LDS read for dQ^T += K^T dS^T; V is read row-wise for dP^T = V dO^T.
-template <int D, bool OUT_F32, int MAXT>
-__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(MAXT >= 256 ? 2 : 1))) void attn_bwd_dq_kernel(AttnParams P) {
+// Query-major dQ kernel.  Same work items as the forward.  A workgroup takes one item (sequence,
+// selection head, query block) and HPW query heads that share its selection (one in per-query-head
+// mode); the K and V tiles of the selected blocks are double-buffered in LDS as whole tiles by
+// asynchronous loads and shared by all wavefronts of the workgroup.  A wavefront owns 32 query rows
+// of one head and, with the key split KS = 2, one 32-key half of every tile (the two partial dQ of a
+// row are added through LDS at the end); Q, dO, LSE and Dr of its rows stay in registers.
+// Transposed products put a query in a C-matrix column: S^T = K Q^T, dP^T = V dO^T, so LSE and Dr are
+// per-lane scalars and dS^T converts to the B operand of dQ^T += K^T dS^T without cross-lane movement;
+// K^T comes from the row-major K tile through the transposing LDS read.
+// The register budget (256) lets two wavefronts share a SIMD: one runs its exponentials while the
+// other runs matrix instructions.  Operands are fetched from LDS in sets of D/16, a set ahead of use.
+template <int D, bool OUT_F32, int KS, int MAXT>
+__global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void attn_bwd_dq_kernel(AttnParams P, int heads) {
+  constexpr int TILE_B = 64 * D * 2, ROW_B = D * 2, NOP = D / 16;
+  constexpr int NMT = 2 / KS;  // 32-key halves of a tile this wavefront computes
   __shared__ __attribute__((aligned(1024))) bf16 tiles[2][2][64 * D];  // [buffer][K, V]
   constexpr int kJ = 256;
   __shared__ int jbuf[kJ];
+  static_assert(KS == 1 || sizeof(tiles) >= (MAXT / 128) * 16 * (D / 32) * 64 * sizeof(float), "partial dQ must fit in the tile buffers");
   BusyTimer timer;
   timer.start(P);
   const int tid = threadIdx.x, nthr = blockDim.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-  const int64_t row = P.work[blockIdx.x];
-  const int hs = (int)(row / P.NQB);
-  const int qb = (int)(row - (int64_t)hs * P.NQB);
-  const int s = P.qb_seq[qb];
-  const int i = qb - P.qb_off[s];
-  const int64_t seq0 = P.cu[s];
-  const int L = P.cu[s + 1] - P.cu[s];
-  const int hh = blockIdx.y * (nthr >> 7) + (wave >> 1), strip = wave & 1;
-  const bool head_ok = P.mode == SB_SELECT_PER_QHEAD || hh < P.G;
+  const WorkItem item = P.items[blockIdx.x];
+  const int hs = item.hs, i = item.i, L = item.len, e0 = item.e0, ntiles = item.ntiles;
+  const int64_t seq0 = item.seq0;
+  const int strip = wave & 1, kh = KS == 2 ? (wave >> 1) & 1 : 0;
+  const int hh = blockIdx.y * (nthr / (128 * KS)) + wave / (2 * KS);  // query head of the group this wavefront works for
+  const bool head_ok = hh < heads;
   const int h = P.mode == SB_SELECT_PER_QHEAD ? hs : hs * P.G + (head_ok ? hh : 0);
   const int g = h / P.G;
   const int qloc = strip * 32 + l32;
   const bool qvalid = head_ok && i * 64 + qloc < L;
   const int64_t tq = seq0 + i * 64 + qloc;
-  const int e0 = P.rowptr[row], ntiles = P.rowptr[row + 1] - e0;
 
   auto stage_indices = [&](int t0) {
     __syncthreads();
@@ -90,31 +96,62 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(MAXT >= 25
     loader.issue(tiles[t & 1][1], P.v, kv0, kvalid, P.Hkv, g);
   };
 
-  bf16x8 qf[D / 16], dof[D / 16];
-  float lse2 = __builtin_inff(), dr = 0.f;  // invalid rows: P = exp2(x - inf) = 0
+  // B operands: column = query lane%32 of the strip, slots = d 16ks + 8hf + (0..7)
+  bf16x8 qf[NOP], dof[NOP];
+  float lse2 = __builtin_inff(), dr = 0.f;  // rows that do not exist: P = exp2(x - inf) = 0
   {
     const bf16* qp = P.q + (tq * P.Hq + h) * D + 8 * hf;
     const bf16* dp = P.d_o + (tq * P.Hq + h) * D + 8 * hf;
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) {
+    for (int ks = 0; ks < NOP; ++ks) {
       qf[ks] = qvalid ? *(const bf16x8*)(qp + 16 * ks) : zero_bf16x8();
       dof[ks] = qvalid ? *(const bf16x8*)(dp + 16 * ks) : zero_bf16x8();
     }
     if (qvalid) {
-      lse2 = P.lse[(int64_t)h * P.T + tq] * 1.4426950408889634f;
+      lse2 = P.lse2[(int64_t)h * P.T + tq];
       dr = P.drow[(int64_t)h * P.T + tq];
     }
   }
   stage_indices(0);
   // everything loaded so far must have landed before the tile loads start (see the forward kernel)
 #pragma unroll
-  for (int ks = 0; ks < D / 16; ++ks) asm volatile("" : "+v"(qf[ks]), "+v"(dof[ks]));
+  for (int ks = 0; ks < NOP; ++ks) asm volatile("" : "+v"(qf[ks]), "+v"(dof[ks]));
   asm volatile("" : "+v"(lse2), "+v"(dr));
   issue(0);
+
+  // LDS byte addresses of this lane's operand reads inside buffer 0, K tile, key half 0
+  const unsigned tiles0 = lds_offset(&tiles[0][0][0]);
+  unsigned row_a[NOP], tr_a[D / 32][2];
+#pragma unroll
+  for (int ks = 0; ks < NOP; ++ks) row_a[ks] = tiles0 + (32 * kh + l32) * ROW_B + 16 * ((2 * ks + hf) ^ chunk_swizzle<D>(l32));
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int r = 8 * half + 4 * hf + ((lane & 15) >> 2), d = 32 * dt + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+      tr_a[dt][half] = tiles0 + (32 * kh + r) * ROW_B + 16 * ((d >> 3) ^ chunk_swizzle<D>(r)) + 2 * (d & 7);
+    }
+  auto ld_rows = [&](bf16x8* dst, unsigned off) __attribute__((always_inline)) {
+#pragma unroll
+    for (int ks = 0; ks < NOP; ++ks) dst[ks] = *(const bf16x8 __attribute__((address_space(3)))*)(row_a[ks] + off);
+  };
+  // A operands of dQ^T += K^T dS^T for the key steps kk0, kk0+1: row = d (32dt + lane%32), slots = keys
+  auto ld_tr = [&](bf16x8* dst, unsigned off, int kk0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt) {
+        const unsigned o = off + (kk0 + q) * 16 * ROW_B;
+        bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(tr_a[dt][0] + o));
+        bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(tr_a[dt][1] + o));
+        dst[q * (D / 32) + dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+  };
 
   f32x16 dqacc[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt) dqacc[dt] = zero16();
+  bf16x8 opA[NOP];
 
   for (int t = 0; t < ntiles; ++t) {
     const bool more = t + 1 < ntiles;
@@ -122,34 +159,54 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(MAXT >= 25
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();  // tile t has landed for everyone; everyone is done with tile t-1
     if (more) issue(t + 1);
-    const bf16* Ks = tiles[t & 1][0];
-    const bf16* Vs = tiles[t & 1][1];
+    const unsigned bo = (t & 1) * 2 * TILE_B;
     const bool diag = t == ntiles - 1;
-    bf16x8 dsb[4];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
+    for (int mt = 0; mt < NMT; ++mt) {  // keys 32(mt + kh) .. +31 of the tile
+      const unsigned ro = bo + mt * 32 * ROW_B;
       f32x16 sacc = zero16(), dpacc = zero16();
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) sacc = mfma32(lds_row8<D>(Ks, 32 * mt + l32, 2 * ks + hf), qf[ks], sacc);
+      for (int ks = 0; ks < NOP; ++ks)
+        sacc = mfma32(*(const bf16x8 __attribute__((address_space(3)))*)(row_a[ks] + ro), qf[ks], sacc);
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) dpacc = mfma32(lds_row8<D>(Vs, 32 * mt + l32, 2 * ks + hf), dof[ks], dpacc);
-      if (diag) {
+      for (int ks = 0; ks < NOP; ++ks)
+        dpacc = mfma32(*(const bf16x8 __attribute__((address_space(3)))*)(row_a[ks] + ro + TILE_B), dof[ks], dpacc);
+      ld_tr(opA, bo, 2 * mt);     // K^T for the dQ step below
+      if (diag) {  // causal mask inside the diagonal block (also removes keys past the end of the sequence)
 #pragma unroll
         for (int v = 0; v < 16; ++v)
-          if (32 * mt + c_row(v, hf) > qloc) sacc[v] = -__builtin_inff();
+          if (32 * (mt + kh) + c_row(v, hf) > qloc) sacc[v] = -__builtin_inff();
       }
+      bf16x8 dsb[2];
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        float pv = fast_exp2(__builtin_fmaf(sacc[v], P.scale_log2e, -lse2));
-        dsb[2 * mt + (v >> 3)][v & 7] = (bf16)(pv * (dpacc[v] - dr));
+        const float pv = fast_exp2(__builtin_fmaf(sacc[v], P.scale_log2e, -lse2));
+        dsb[v >> 3][v & 7] = (bf16)(pv * (dpacc[v] - dr));
       }
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt) dqacc[dt] = mfma32(opA[q * (D / 32) + dt], dsb[q], dqacc[dt]);
     }
-#pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) dqacc[dt] = mfma32(lds_tr_operand<D>(Ks, kk, dt, lane), dsb[kk], dqacc[dt]);
   }
-  if (qvalid) {
+  if (KS == 2) {  // add the two key halves of every row: the kh = 1 wavefront hands its partial over
+    float* xbuf = (float*)&tiles[0][0][0] + (size_t)(wave >> 2) * 2 * (16 * (D / 32) * 64) + (size_t)strip * (16 * (D / 32) * 64);
+    __syncthreads();  // everyone is done with the tile buffers
+    if (kh == 1) {
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) xbuf[(16 * dt + v) * 64 + lane] = dqacc[dt][v];
+    }
+    __syncthreads();
+    if (kh == 0) {
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) dqacc[dt][v] += xbuf[(16 * dt + v) * 64 + lane];
+    }
+  }
+  if (qvalid && kh == 0) {
     const int64_t obase = (tq * P.Hq + h) * D;
 #pragma unroll
     for (int dt = 0; dt < D / 32; ++dt)
@@ -527,16 +584,16 @@ int convert_f32_to_bf16(const void* src, void* dst, int64_t n, hipStream_t st);
 
 template <int D, bool F32>
 static int launch_bwd(const Geo& g, const AttnParams& P, hipStream_t st) {
-  // query-major dQ
-  const int G = g.mode == SB_SELECT_PER_QHEAD ? 1 : g.G;
-  const int parts = (G + 3) / 4, hpp = (G + parts - 1) / parts;
-  AttnParams Pq = P;
-  Pq.work = P.work;  // forward work list
-  dim3 grid((unsigned)(g.Hs * g.NQB), (unsigned)parts), block((unsigned)(128 * hpp));
+  // query-major dQ: one workgroup per (item, part of the item's query heads); 2 * KS wavefronts per head
+  const int heads = g.mode == SB_SELECT_PER_QHEAD ? 1 : g.G;
+  const int parts = (heads + 3) / 4, hpp = (heads + parts - 1) / parts;  // heads per workgroup: 1..4
+  const int64_t n_items = (int64_t)g.Hs * g.NQB;
+  if (n_items > 0x7fffffffll) { set_error("too many work items for one launch"); return SB_ERR_INVALID_ARG; }
+  dim3 grid((unsigned)n_items, (unsigned)parts);
   KernelTimer kt(K_BWD_DQ, st);
-  if (hpp == 1) hipLaunchKernelGGL((attn_bwd_dq_kernel<D, F32, 128>), grid, block, 0, st, Pq);
-  else if (hpp == 2) hipLaunchKernelGGL((attn_bwd_dq_kernel<D, F32, 256>), grid, block, 0, st, Pq);
-  else hipLaunchKernelGGL((attn_bwd_dq_kernel<D, F32, 512>), grid, block, 0, st, Pq);
+  if (hpp == 1) hipLaunchKernelGGL((attn_bwd_dq_kernel<D, F32, 2, 256>), grid, dim3(256), 0, st, P, heads);
+  else if (hpp == 2) hipLaunchKernelGGL((attn_bwd_dq_kernel<D, F32, 2, 512>), grid, dim3(512), 0, st, P, heads);
+  else hipLaunchKernelGGL((attn_bwd_dq_kernel<D, F32, 1, 512>), grid, dim3(128 * hpp), 0, st, P, heads);
   SB_LAUNCH_CHECK("attn_bwd_dq_kernel");
   return SB_OK;
 }
@@ -587,6 +644,7 @@ extern "C" int sb_sparse_attn_bwd(const sb_problem* p, const void* q, const void
   float* lse2 = (float*)(wb + wo.lse2);
   P.lse = (float*)lse; P.drow = drow; P.lse2 = lse2; P.dq = dq; P.dk = dk; P.dv = dv;
   P.rowptr = sel_rowptr; P.idx = sel_idx;
+  P.items = (const WorkItem*)(pb + po.items);
   P.bitmap = (const uint32_t*)(pb + po.bitmap);
   P.cu = t.cu; P.qb_off = t.qb_off; P.qb_seq = t.qb_seq; P.bm_off = t.bm_off;
   P.NQB = g.NQB; P.T = g.T; P.Hq = g.Hq; P.Hkv = g.Hkv; P.G = g.G; P.Hs = g.Hs; P.mode = g.mode;

@@ -159,17 +159,16 @@ struct TileLoader {
   static constexpr int RPI = 64 / C;   // rows covered by one wavefront-wide load
   static constexpr int LPT = D / 16;   // loads per loader wavefront per tile
   unsigned voff[LPT];
-  int row[LPT], chunk_bytes[LPT];
+  int rl, pc;  // row within a load's group of RPI rows, 16-byte chunk of this lane
   int wave;
   __device__ inline void init(int H, int wave_, int lane) {
     wave = wave_;
-    const int rl = lane / C, pc = lane % C;
+    rl = lane / C;
+    pc = lane % C;
 #pragma unroll
     for (int a = 0; a < LPT; ++a) {
       const int r = ((wave & 1) + 2 * a) * RPI + rl;
-      row[a] = r;
-      chunk_bytes[a] = 16 * (pc ^ chunk_swizzle<D>(r));
-      voff[a] = (unsigned)(r * H * D * 2 + chunk_bytes[a]);
+      voff[a] = (unsigned)(r * H * D * 2 + 16 * (pc ^ chunk_swizzle<D>(r)));
     }
   }
   // Issue the copy of rows row0 .. row0+63 (head h) of `src` into `slot`.  Rows >= valid repeat the
@@ -192,8 +191,10 @@ struct TileLoader {
                      : : "v"(voff[a]), "s"(ts), "s"(base + ((wave & 1) + 2 * a) * 1024) : "memory", "m0");
     } else {
 #pragma unroll
-      for (int a = 0; a < LPT; ++a)
-        dma16(tile + (int64_t)min(row[a], valid - 1) * H * D * 2 + chunk_bytes[a], base + ((wave & 1) + 2 * a) * 1024);
+      for (int a = 0; a < LPT; ++a) {  // ragged tile (rare): the lane offsets are recomputed instead of being kept in registers
+        const int r = ((wave & 1) + 2 * a) * RPI + rl;
+        dma16(tile + (int64_t)min(r, valid - 1) * H * D * 2 + 16 * (pc ^ chunk_swizzle<D>(r)), base + ((wave & 1) + 2 * a) * 1024);
+      }
     }
   }
 };
@@ -214,18 +215,17 @@ struct StripLoader {
   static constexpr int LPS = 32 / RPI;   // loads per strip
   static_assert(LPS % 4 == 0, "loads are issued in groups of four");
   unsigned voff[LPS];                    // lane offset of load a, minus 1024 * (a % 4)
-  int row[LPS], chunk_bytes[LPS];
+  int rl, pc;                            // row within a load's group of RPI rows, 16-byte chunk of this lane
   int pitch;                             // bytes between consecutive rows
   __device__ inline void init(int H, int lane) {
-    const int rl = lane / C, pc = lane % C;
+    rl = lane / C;
+    pc = lane % C;
     pitch = H * D * 2;
 #pragma unroll
     for (int a = 0; a < LPS; ++a) {
       const int r = a * RPI + rl;
-      row[a] = r;
-      chunk_bytes[a] = 16 * (pc ^ chunk_swizzle<D>(r));
       // r * pitch >= 1024 * a * H, so the bias never makes the offset negative
-      voff[a] = (unsigned)(r * pitch + chunk_bytes[a] - 1024 * (a & 3));
+      voff[a] = (unsigned)(r * pitch + 16 * (pc ^ chunk_swizzle<D>(r)) - 1024 * (a & 3));
     }
   }
   // all 32 rows exist; `strip` must be wave-uniform
@@ -255,7 +255,10 @@ struct StripLoader {
       issue_full(slot, strip);
     } else {
 #pragma unroll
-      for (int a = 0; a < LPS; ++a) dma16(strip + (int64_t)min(row[a], valid - 1) * pitch + chunk_bytes[a], slot + a * 1024);
+      for (int a = 0; a < LPS; ++a) {  // ragged strip (rare): the lane offsets are recomputed instead of being kept in registers
+        const int r = a * RPI + rl;
+        dma16(strip + (int64_t)min(r, valid - 1) * pitch + 16 * (pc ^ chunk_swizzle<D>(r)), slot + a * 1024);
+      }
     }
   }
 };
