@@ -4,8 +4,8 @@
 //   P  = exp(scale * S - LSE),  dP = dO V^T,  dS = P * (dP - Dr)
 //   dQ = scale * dS K          query-major kernel, same work items and tile walk as the forward
 //   dK = scale * dS^T Q, dV = P^T dO   key-major kernel: one workgroup owns key block (s, g, j),
-//        keeps its K/V strip in registers, walks the query blocks that kept j (transpose bitmap,
-//        ascending) for every query head of the KV group and accumulates in registers; each output
+//        keeps its K/V strip in registers, walks the query blocks that kept j (transpose bitmap, last
+//        query block first) for every query head of the KV group and accumulates in registers; each output
 //        element is written once, in a fixed order, so the result is deterministic.
 #include <type_traits>
 
@@ -119,7 +119,8 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
   asm volatile("" : "+v"(lse2), "+v"(dr));
   issue(0);
 
-  // LDS byte addresses of this lane's operand reads inside buffer 0, K tile, key half 0
+  // LDS byte addresses of this lane's operand reads inside the current buffer's K tile, key half kh;
+  // they move to the other buffer once per tile, everything else is a compile-time offset
   const unsigned tiles0 = lds_offset(&tiles[0][0][0]);
   unsigned row_a[NOP], tr_a[D / 32][2];
 #pragma unroll
@@ -131,27 +132,21 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
       const int r = 8 * half + 4 * hf + ((lane & 15) >> 2), d = 32 * dt + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
       tr_a[dt][half] = tiles0 + (32 * kh + r) * ROW_B + 16 * ((d >> 3) ^ chunk_swizzle<D>(r)) + 2 * (d & 7);
     }
-  auto ld_rows = [&](bf16x8* dst, unsigned off) __attribute__((always_inline)) {
-#pragma unroll
-    for (int ks = 0; ks < NOP; ++ks) dst[ks] = *(const bf16x8 __attribute__((address_space(3)))*)(row_a[ks] + off);
+  auto ld_row = [&](int ks, unsigned off) __attribute__((always_inline)) {
+    return *(const bf16x8 __attribute__((address_space(3)))*)(row_a[ks] + off);
   };
-  // A operands of dQ^T += K^T dS^T for the key steps kk0, kk0+1: row = d (32dt + lane%32), slots = keys
-  auto ld_tr = [&](bf16x8* dst, unsigned off, int kk0) __attribute__((always_inline)) {
-#pragma unroll
-    for (int q = 0; q < 2; ++q)
-#pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt) {
-        const unsigned o = off + (kk0 + q) * 16 * ROW_B;
-        bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(tr_a[dt][0] + o));
-        bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(tr_a[dt][1] + o));
-        dst[q * (D / 32) + dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      }
+  // A operand of dQ^T += K^T dS^T: row = d (32dt + lane%32), slots = keys 16kk + 8(e/4) + 4hf + e%4 of this wavefront's rows
+  auto ld_tr = [&](int kk, int dt, unsigned off) __attribute__((always_inline)) {
+    const unsigned o = off + kk * 16 * ROW_B;
+    bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(tr_a[dt][0] + o));
+    bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(tr_a[dt][1] + o));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   };
 
   f32x16 dqacc[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt) dqacc[dt] = zero16();
-  bf16x8 opA[NOP];
+  bf16x8 op[NOP];  // one rotating operand set: a register is refilled for the next contraction as soon as it has been consumed
 
   for (int t = 0; t < ntiles; ++t) {
     const bool more = t + 1 < ntiles;
@@ -159,19 +154,43 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();  // tile t has landed for everyone; everyone is done with tile t-1
     if (more) issue(t + 1);
-    const unsigned bo = (t & 1) * 2 * TILE_B;
+    if (t > 0) {  // the operand addresses follow the tile into the other buffer
+      const int dl = (t & 1) ? 2 * TILE_B : -2 * TILE_B;
+#pragma unroll
+      for (int ks = 0; ks < NOP; ++ks) row_a[ks] += dl;
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt) { tr_a[dt][0] += dl; tr_a[dt][1] += dl; }
+    }
     const bool diag = t == ntiles - 1;
 #pragma unroll
     for (int mt = 0; mt < NMT; ++mt) {  // keys 32(mt + kh) .. +31 of the tile
-      const unsigned ro = bo + mt * 32 * ROW_B;
+      const unsigned ro = mt * 32 * ROW_B;
+#pragma unroll
+      for (int ks = 0; ks < NOP; ++ks) op[ks] = ld_row(ks, ro);  // K rows
+      __builtin_amdgcn_sched_barrier(0);
       f32x16 sacc = zero16(), dpacc = zero16();
 #pragma unroll
-      for (int ks = 0; ks < NOP; ++ks)
-        sacc = mfma32(*(const bf16x8 __attribute__((address_space(3)))*)(row_a[ks] + ro), qf[ks], sacc);
+      for (int ks = 0; ks < NOP; ++ks) {  // S^T = K Q^T, refilling every operand register with the V row operand
+        sacc = mfma32(op[ks], qf[ks], sacc);
+        op[ks] = ld_row(ks, ro + TILE_B);
+      }
 #pragma unroll
-      for (int ks = 0; ks < NOP; ++ks)
-        dpacc = mfma32(*(const bf16x8 __attribute__((address_space(3)))*)(row_a[ks] + ro + TILE_B), dof[ks], dpacc);
-      ld_tr(opA, bo, 2 * mt);     // K^T for the dQ step below
+      for (int i_ = 0; i_ < NOP; ++i_) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int ks = 0; ks < NOP; ++ks) {  // dP^T = V dO^T, refilling with the K^T operands of the dQ step
+        dpacc = mfma32(op[ks], dof[ks], dpacc);
+        op[ks] = ld_tr(2 * mt + ks / (D / 32), ks % (D / 32), 0);
+      }
+#pragma unroll
+      for (int i_ = 0; i_ < NOP; ++i_) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
       if (diag) {  // causal mask inside the diagonal block (also removes keys past the end of the sequence)
 #pragma unroll
         for (int v = 0; v < 16; ++v)
@@ -186,7 +205,7 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
 #pragma unroll
       for (int q = 0; q < 2; ++q)
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt) dqacc[dt] = mfma32(opA[q * (D / 32) + dt], dsb[q], dqacc[dt]);
+        for (int dt = 0; dt < D / 32; ++dt) dqacc[dt] = mfma32(op[q * (D / 32) + dt], dsb[q], dqacc[dt]);
     }
   }
   if (KS == 2) {  // add the two key halves of every row: the kh = 1 wavefront hands its partial over
@@ -238,9 +257,10 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
 //   S,dP(half 0);  S,dP(half 1) | P,dS(half 0);  dV,dK(half 0) | P,dS(half 1);  dV,dK(half 1)
 // Tiles that need a mask (the diagonal block, a ragged last query block) take a separate
 // instantiation of the tile body, so the common path has no per-element selects or branches.
-// The column's tiles are visited query block by query block (ascending), all query heads of the KV
-// group at one query block before the next: concurrent columns of one KV head (same XCD) then ask
-// for the same Q/dO tiles at about the same time and meet them in that XCD's L2.
+// The column's tiles are visited query block by query block, from the sequence's last query block
+// down to the diagonal, all query heads of the KV group at one query block before the next:
+// concurrent columns of one KV head (same XCD) start at the same query block, advance at a similar
+// pace and so ask for the same Q/dO tiles at about the same time and meet them in that XCD's L2.
 template <int D, bool OUT_F32>
 __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void attn_bwd_dkv_kernel(AttnParams P) {
   constexpr int TILE_B = 64 * D * 2;  // bytes of one Q or dO tile
@@ -377,9 +397,11 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
   int tt = 0;                                // tiles processed so far: tile tt lives in buffer tt & 1
   for (int sel0 = 0; sel0 < nsel; sel0 += 8) {                  // selection heads in groups of 8
     const int ns8 = min(8, nsel - sel0);
-    for (int w0 = (j >> 5) & ~(kCW - 1); w0 < words; w0 += kCW) {  // chunks of kCW bitmap words
+    for (int w0 = ((words - 1) & ~(kCW - 1)); w0 >= ((j >> 5) & ~(kCW - 1)); w0 -= kCW) {  // chunks of kCW bitmap words, last first
       const int wn = min(kCW, words - w0);
-      // ---- the chunk's tile list: entry = (query block - 32 w0) * 8 + head, ordered by query block, then head
+      // ---- the chunk's tile list: entry = (query block - 32 w0) * 8 + head, ordered by query block, then head.
+      // The list is walked backwards (last query block first): every column of a sequence then starts at
+      // the same query block and, selecting at a similar density, stays close to its neighbours.
       __syncthreads();
       for (int a = tid; a < ns8 * kCW; a += 128) {
         const int sel = a / kCW, w = a % kCW;
@@ -417,7 +439,7 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
       __syncthreads();
       const int ntl = __builtin_amdgcn_readfirstlane(ntl_s);
       if (ntl == 0) continue;
-      // the diagonal tiles (query block j itself) are the first of the list: count them
+      // the diagonal tiles (query block j itself) are the first of the list, i.e. the last to be processed: count them
       int nd = 0;
       if (j >= 32 * w0 && j < 32 * (w0 + kCW)) {
         for (int sel = 0; sel < ns8; ++sel) nd += (int)((bm_s[sel][(j >> 5) - w0] >> (j & 31)) & 1u) * hpe;
@@ -426,7 +448,7 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) asm volatile("" : "+v"(kf[ks]), "+v"(vf[ks]));
       auto entry = [&](int t, int& i, int& h) __attribute__((always_inline)) {
-        const int e = __builtin_amdgcn_readfirstlane((int)tl_s[t]);
+        const int e = __builtin_amdgcn_readfirstlane((int)tl_s[ntl - 1 - t]);
         i = 32 * w0 + (e >> 3);
         h = g * P.G + sel0 + (e & 7);
       };
@@ -453,7 +475,7 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
       auto run_tiles = [&](auto diag_c, int tb, int te) __attribute__((always_inline)) {
         constexpr bool DIAG = decltype(diag_c)::value;
         for (int t = tb; t < te; ++t, ++tt) {
-          const int e2 = t + 2 < ntl ? (int)tl_s[t + 2] : 0;
+          const int e2 = t + 2 < ntl ? (int)tl_s[ntl - 3 - t] : 0;
           // stage 0: S(queries 0..31)
           ld_rows(opB, TILE_B);
           sacc[0] = zero16();
@@ -554,8 +576,8 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
           SB_STAGE_FENCE();
         }
       };
-      run_tiles(std::true_type(), 0, nd);
-      run_tiles(std::false_type(), nd, ntl);
+      run_tiles(std::false_type(), 0, ntl - nd);
+      run_tiles(std::true_type(), ntl - nd, ntl);
     }
   }
 #undef SB_PIPE
