@@ -52,19 +52,21 @@ def uniform01(seed: int, tid: int, start: int, count: int) -> np.ndarray:
 
 
 def _normal_chunk(args):
-    seed, tid, s, n, out = args
+    seed, tid, s, n, out, to_bf16 = args
     inv = 1.0 / 16777216.0
     z = raw_u64(seed, tid, s, n)
     u1 = ((z >> np.uint64(40)).astype(np.float64) + 0.5) * inv
     u2 = ((z & np.uint64(0xFFFFFF)).astype(np.float64) + 0.5) * inv
-    out[s:s + n] = (np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)).astype(np.float32)
+    x = (np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)).astype(np.float32)
+    out[s:s + n] = round_to_bf16(x) if to_bf16 else x
 
 
-def normal_f32(seed: int, tid: int, count: int, chunk: int = 1 << 21) -> np.ndarray:
-    """`count` i.i.d. N(0,1) values as float32 (computed in float64, then rounded).
-    Chunks are independent (counter-based), so they are filled by a small thread pool."""
+def normal_f32(seed: int, tid: int, count: int, chunk: int = 1 << 18, to_bf16: bool = False) -> np.ndarray:
+    """`count` i.i.d. N(0,1) values as float32 (computed in float64, then rounded; with `to_bf16`
+    rounded once more to the nearest bfloat16 value).  Chunks are independent (counter-based), so
+    they are filled by a small thread pool, each chunk small enough to stay in cache."""
     out = np.empty(count, dtype=np.float32)
-    jobs = [(seed, tid, s, min(chunk, count - s), out) for s in range(0, count, chunk)]
+    jobs = [(seed, tid, s, min(chunk, count - s), out, to_bf16) for s in range(0, count, chunk)]
     if len(jobs) <= 1:
         for j in jobs:
             _normal_chunk(j)
@@ -141,8 +143,7 @@ class Workload:
         shp_q, shp_k = (self.T, self.Hq, self.D), (self.T, self.Hkv, self.D)
         out = {}
         for name, tid, shp in (("q", TID_Q, shp_q), ("k", TID_K, shp_k), ("v", TID_V, shp_k), ("do", TID_DO, shp_q)):
-            x = normal_f32(self.seed, tid, int(np.prod(shp))).reshape(shp)
-            out[name] = round_to_bf16(x) if self.dtype == "bf16" else x
+            out[name] = normal_f32(self.seed, tid, int(np.prod(shp)), to_bf16=self.dtype == "bf16").reshape(shp)
         return out
 
     def __repr__(self):

@@ -1,6 +1,9 @@
-"""GPU parity at the benchmark's full size (configs[1]: packed 32768 tokens, 32/8 heads, D=128) in
-the launch configuration bench.py times.  The CPU checker evaluates sampled outputs one by one:
-score rows, query rows (O, LSE, dQ) and whole key blocks (dK, dV); the selection is compared in full."""
+"""GPU parity at full size: the benchmark's workload (configs[1]: packed 32768 tokens, 32/8 heads,
+D=128) in the launch configuration bench.py times, and the larger configurations (65536 tokens with
+7 query heads per KV head, one 131072-token sequence, the skewed 262144-token batch).  The CPU
+checker evaluates sampled outputs one by one: score rows, query rows (O, LSE, dQ) and whole key
+blocks (dK, dV); the selection is compared in full (configs[1]) or for sampled (sequence, head)
+pairs."""
 import numpy as np
 import pytest
 import torch
@@ -59,3 +62,78 @@ def test_config2_sampled(mode):
         b = min(a + 64, int(w.cu[s + 1]))
         print((s, g, j), "dK", check_close("dK", to_host_f32(r.dk[a:b, g]), dK[: b - a]),
               "dV", check_close("dV", to_host_f32(r.dv[a:b, g]), dV[: b - a]), flush=True)
+
+
+def _selection_of_head(r, po, got_scores, s, hs):
+    """The checker's selection for one (sequence, selection head), from the GPU's scores of that head."""
+    n = po.nblk[s]
+    L = int(r.w.cu[s + 1] - r.w.cu[s])
+    one = orc.Problem(np.array([0, L], dtype=np.int32), 1, 1, r.w.D, r.w.B, 0)
+    sc = got_scores[po.score_off[s] + hs * n * n: po.score_off[s] + (hs + 1) * n * n]
+    rp, idx = orc.select_topk(one, sc, r.topk[s:s + 1])
+    row0 = hs * po.NQB + int(po.qb_off[s])
+    a, b = int(r.rowptr_h[row0]), int(r.rowptr_h[row0 + n])
+    return rp, idx, r.rowptr_h[row0: row0 + n + 1] - a, r.idx_h[a:b]
+
+
+def _sampled_check(w, mode, n_rows, kv_picks, sel_pairs, seed=7):
+    r = Run(w, mode)
+    po, lay = r.opb, r.pb.layout
+    rng = np.random.default_rng(seed)
+    got_scores = r.scores.cpu().numpy()[: lay.scores_elems]
+    q, k, v, do = r.oracle_inputs()
+    for _ in range(6):  # score rows
+        s = int(rng.integers(0, w.S)); hs = int(rng.integers(0, po.Hs)); i = int(rng.integers(0, max(po.nblk[s], 1)))
+        if po.nblk[s] == 0:
+            continue
+        ref = orc.block_scores_row(po, q, k, r.scale, s, hs, i)
+        n = po.nblk[s]
+        got = got_scores[po.score_off[s] + (hs * n + i) * n: po.score_off[s] + (hs * n + i + 1) * n]
+        assert np.array_equal(np.isneginf(got), np.isneginf(ref))
+        fin = np.isfinite(ref)
+        if fin.any():
+            assert np.abs(got[fin] - ref[fin]).max() <= 2e-5 * max(1e-3, np.abs(ref[fin]).max())
+    for (s, hs) in sel_pairs:  # selection of whole heads, bit-exact on the GPU's scores
+        rp, idx, grp, gidx = _selection_of_head(r, po, got_scores, s, hs)
+        assert np.array_equal(rp, grp) and np.array_equal(idx, gidx), f"selection differs for sequence {s}, head {hs}"
+    # plan: every item and every column once
+    pv = sb.plan_views(r.pb, r.plan)
+    assert np.array_equal(np.sort(pv["work_fwd"]), np.arange(lay.sel_rows))
+    assert np.all(np.diff(np.diff(r.rowptr_h)[pv["work_fwd"]]) <= 0)
+    assert np.array_equal(np.sort(pv["work_bwd"]), np.arange(w.Hkv * lay.num_qblocks))
+    assert pv["colcost"].sum() == lay.sel_nnz * (1 if mode == 0 else w.Hq // w.Hkv)
+    # sampled query rows, including the first and last rows of sequences
+    ends = np.concatenate([w.cu[:-1], w.cu[1:] - 1])[:64]
+    toks = np.concatenate([rng.integers(0, w.T, size=n_rows), ends]).astype(np.int32)
+    heads = rng.integers(0, w.Hq, size=toks.size).astype(np.int32)
+    O, LSE, dQ = orc.attn_rows(po, q, k, v, do, r.rowptr_h, r.idx_h, r.scale, toks, heads)
+    ti, hi = torch.from_numpy(toks.astype(np.int64)), torch.from_numpy(heads.astype(np.int64))
+    print("O", check_close("O", to_host_f32(r.o.cpu()[ti, hi]), O), "dQ", check_close("dQ", to_host_f32(r.dq.cpu()[ti, hi]), dQ), flush=True)
+    assert np.abs(r.lse.cpu().numpy()[heads, toks] - LSE).max() <= 1e-2
+    for (s, g, j) in kv_picks:  # whole key blocks
+        dK, dV = orc.attn_bwd_kvblock(po, q, k, v, do, r.rowptr_h, r.idx_h, r.scale, s, g, j)
+        a = int(w.cu[s]) + j * 64
+        b = min(a + 64, int(w.cu[s + 1]))
+        print((s, g, j), "dK", check_close("dK", to_host_f32(r.dk[a:b, g]), dK[: b - a]),
+              "dV", check_close("dV", to_host_f32(r.dv[a:b, g]), dV[: b - a]), flush=True)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_config3_sampled(mode):
+    """65536 tokens, 28 query heads on 4 KV heads (7 per group), keep ratio 0.05 .. 0.3"""
+    w = synth.config3(0)
+    s_long = int(np.argmax(w.lens))
+    n = (w.lens[s_long] + 63) // 64
+    _sampled_check(w, mode, 96, [(s_long, 0, 3), (s_long, 3, n // 2), (s_long, 1, n - 1)], [(s_long, 0), (0, 1)])
+
+
+def test_config4_sampled():
+    """one sequence of 131072 tokens, fixed budget of 32 blocks"""
+    w = synth.config4(0)
+    _sampled_check(w, 0, 96, [(0, 0, 1), (0, 7, 1024), (0, 3, 2047)], [(0, 5)])
+
+
+def test_config5_sampled():
+    """262144 tokens: one 131072-token sequence at keep ratio 0.05 plus short, dense sequences"""
+    w = synth.config5(0)
+    _sampled_check(w, 0, 96, [(0, 2, 40), (0, 5, 2047), (1, 0, 0), (w.S - 1, 7, 0)], [(0, 9), (w.S // 2, 3)])
