@@ -83,6 +83,7 @@ typedef struct sb_layout {
   int64_t scores_ws_bytes, select_ws_bytes, fwd_ws_bytes, bwd_ws_bytes; /* bytes of the `ws` arguments */
   int64_t attended_pairs_per_head_sum; /* sum over query heads of unmasked (query,key) pairs,
                                           the diagonal block counted as its causal triangle */
+  int64_t coverage_ws_bytes; /* bytes of the `ws` argument of sb_score_coverage */
 } sb_layout;
 
 /* Host only.  Validates the problem and fills `out`. */
@@ -135,6 +136,50 @@ int sb_sparse_attn_bwd(const sb_problem *p, const void *q, const void *k, const 
                        const float *lse, const void *d_o, const int32_t *sel_rowptr, const int32_t *sel_idx,
                        const void *plan, void *dq, void *dk, void *dv, void *ws, void *stream);
 
+/* ---- budget controller (paper sections 4.1 and 4.2): what sets topk[] before the calls above ----
+ *
+ * Coverage curves of the routing scores (section 4.1, Eq. 4).  For query block i of sequence s and one
+ * selection head, the scores of the earlier blocks j < i are normalised by a softmax and sorted in
+ * descending order into importance scores r_1 >= r_2 >= ... (sum 1); a budget k keeps the diagonal
+ * block plus the k-1 best earlier blocks, so the row covers the sum of its min(k-1, i) largest r.
+ * C_s(k), k = 1..n_s, is the mean of that over the sequence's query blocks and selection heads:
+ * non-decreasing, C_s(1) = 1/n_s, C_s(n_s) = 1.  `scores`: dev, as written by sb_block_scores (finite
+ * for j < i).  coverage_out: dev, NQB floats, C_s(k) at qb_off[s] + k - 1.  ws: dev, coverage_ws_bytes.
+ * Deterministic (fixed summation order). */
+int sb_score_coverage(const sb_problem *p, const float *scores, float *coverage_out, void *ws, void *stream);
+
+/* Profiled latency table M[x, k] (section 4.2, Eq. 10): latency[a*num_budgets + b] is the measured
+ * latency at length lengths[a] (tokens) and budget budgets[b] (blocks); both grids strictly
+ * increasing.  All pointers are host pointers; the caller owns them. */
+typedef struct sb_perf_table {
+  int32_t num_lengths, num_budgets;
+  const float *lengths;
+  const float *budgets;
+  const float *latency;
+} sb_perf_table;
+
+/* Host only.  Perf.predict (Eq. 8): the table interpolated linearly in length and in budget, clamped
+ * at its edges. */
+int sb_perf_predict(const sb_perf_table *t, double length, double budget, double *latency_out);
+
+/* Host only.  Perf.align (Eq. 9): the largest integer budget in 1..max_budget whose predicted latency
+ * does not exceed target_latency; 1 if none does. */
+int sb_perf_align(const sb_perf_table *t, double length, double target_latency, int32_t max_budget,
+                  int32_t *budget_out);
+
+/* Host only.  Workload-aware dynamic sparsity tuning (section 4.1, Algorithm 1) with every packed
+ * sequence as one micro-batch.  p->topk_host are the base budgets k_base.  T_anchor is the minimum,
+ * mean or maximum (Eq. 3) of the predicted latencies at the base budgets; k_anchor = Perf.align(L_s,
+ * T_anchor) in 1..n_s; the final budget is k_anchor unless C_s(k_base) - C_s(k_anchor) exceeds
+ * threshold_p (Eq. 5), in which case it is the smallest k with C_s(k_base) - C_s(k) <= threshold_p.
+ * coverage_host: host copy of sb_score_coverage's output.  topk_final_out: host [S];
+ * topk_anchor_out (host [S]) and t_anchor_out may be null.  Empty sequences keep their base budget. */
+#define SB_ANCHOR_MIN 0
+#define SB_ANCHOR_MEAN 1
+#define SB_ANCHOR_MAX 2
+int sb_dst_tune(const sb_problem *p, const float *coverage_host, const sb_perf_table *perf, int anchor,
+                double threshold_p, int32_t *topk_final_out, int32_t *topk_anchor_out, double *t_anchor_out);
+
 /* Instrumentation (measurement only; off by default).  `flag` is a bit set:
  *   SB_INSTR_CU_BUSY  the attention kernels add, for every workgroup, its run time in ticks of the
  *                     100 MHz constant clock to a per-compute-unit slot inside `ws`; sb_read_cu_busy
@@ -147,7 +192,7 @@ int sb_sparse_attn_bwd(const sb_problem *p, const void *q, const void *k, const 
 #define SB_CU_SLOTS 512
 #define SB_INSTR_CU_BUSY 1
 #define SB_INSTR_KERNEL_EVENTS 2
-#define SB_NUM_KERNELS 8 /* pool, score, topk, plan, fwd, bwd_prep, bwd_dq, bwd_dkv */
+#define SB_NUM_KERNELS 9 /* pool, score, topk, plan, fwd, bwd_prep, bwd_dq, bwd_dkv, coverage */
 int sb_set_instrumentation(int flag);
 int sb_read_cu_busy(const void *ws, uint64_t *busy_out_host, void *stream);
 int sb_read_kernel_times(double *total_ms_host, int64_t *launches_host);

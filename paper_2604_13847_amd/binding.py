@@ -21,7 +21,8 @@ SB_SELECT_PER_QHEAD, SB_SELECT_PER_KVGROUP = 0, 1
 SB_CU_SLOTS = 512
 
 EXPORTS = ["sb_get_layout", "sb_keep_ratio_to_topk", "sb_sel_rowptr_host", "sb_block_scores", "sb_select_topk",
-           "sb_plan_worklist", "sb_sparse_attn_fwd", "sb_sparse_attn_bwd", "sb_set_instrumentation", "sb_read_cu_busy", "sb_read_kernel_times",
+           "sb_plan_worklist", "sb_sparse_attn_fwd", "sb_sparse_attn_bwd", "sb_score_coverage", "sb_perf_predict", "sb_perf_align", "sb_dst_tune",
+           "sb_set_instrumentation", "sb_read_cu_busy", "sb_read_kernel_times",
            "sb_last_error", "sb_version"]
 
 
@@ -36,7 +37,12 @@ class sb_problem(C.Structure):
 class sb_layout(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("num_qblocks", "sel_heads", "scores_elems", "pooled_elems", "sel_rows", "sel_nnz",
                                          "plan_bytes", "scores_ws_bytes", "select_ws_bytes", "fwd_ws_bytes", "bwd_ws_bytes",
-                                         "attended_pairs_per_head_sum")]
+                                         "attended_pairs_per_head_sum", "coverage_ws_bytes")]
+
+
+class sb_perf_table(C.Structure):
+    _fields_ = [("num_lengths", C.c_int32), ("num_budgets", C.c_int32), ("lengths", C.c_void_p), ("budgets", C.c_void_p),
+                ("latency", C.c_void_p)]
 
 
 _lib = None
@@ -167,8 +173,54 @@ def sb_sparse_attn_bwd(pb: Problem, q, k, v, o, lse, d_o, sel_rowptr, sel_idx, p
     return dq, dk, dv
 
 
+SB_ANCHOR_MIN, SB_ANCHOR_MEAN, SB_ANCHOR_MAX = 0, 1, 2
+
+
+def sb_score_coverage(pb: Problem, scores, ws=None):
+    """Coverage curves C_s(k) of the routing scores: NQB floats on the device."""
+    cov = torch.empty(max(pb.layout.num_qblocks, 1), dtype=torch.float32, device=scores.device)
+    ws = ws if ws is not None else _bytes(pb.layout.coverage_ws_bytes, scores.device)
+    _check(lib().sb_score_coverage(pb.ref(), _ptr(scores), _ptr(cov), _ptr(ws), _stream()))
+    return cov
+
+
+class PerfTable:
+    """Holds sb_perf_table plus the host arrays it points to."""
+
+    def __init__(self, lengths, budgets, latency):
+        self.lengths = np.ascontiguousarray(lengths, dtype=np.float32)
+        self.budgets = np.ascontiguousarray(budgets, dtype=np.float32)
+        self.latency = np.ascontiguousarray(latency, dtype=np.float32).reshape(len(self.lengths), len(self.budgets))
+        self.c = sb_perf_table(len(self.lengths), len(self.budgets), self.lengths.ctypes.data, self.budgets.ctypes.data,
+                               self.latency.ctypes.data)
+
+    def ref(self):
+        return C.byref(self.c)
+
+
+def sb_perf_predict(tab: PerfTable, length, budget) -> float:
+    out = C.c_double()
+    _check(lib().sb_perf_predict(tab.ref(), C.c_double(length), C.c_double(budget), C.byref(out)))
+    return out.value
+
+
+def sb_perf_align(tab: PerfTable, length, target, max_budget) -> int:
+    out = C.c_int32()
+    _check(lib().sb_perf_align(tab.ref(), C.c_double(length), C.c_double(target), int(max_budget), C.byref(out)))
+    return out.value
+
+
+def sb_dst_tune(pb: Problem, coverage_host, tab: PerfTable, anchor, threshold_p):
+    """Algorithm 1 for every sequence; pb's topk are the base budgets.  Returns (k_final, k_anchor, T_anchor)."""
+    cov = np.ascontiguousarray(coverage_host, dtype=np.float32)
+    kf, ka = np.zeros(max(pb.S, 1), dtype=np.int32), np.zeros(max(pb.S, 1), dtype=np.int32)
+    ta = C.c_double()
+    _check(lib().sb_dst_tune(pb.ref(), _ptr(cov), tab.ref(), int(anchor), C.c_double(threshold_p), _ptr(kf), _ptr(ka), C.byref(ta)))
+    return kf[: pb.S], ka[: pb.S], ta.value
+
+
 SB_INSTR_CU_BUSY, SB_INSTR_KERNEL_EVENTS = 1, 2
-KERNEL_NAMES = ["pool", "score", "topk", "plan", "fwd", "bwd_prep", "bwd_dq", "bwd_dkv"]
+KERNEL_NAMES = ["pool", "score", "topk", "plan", "fwd", "bwd_prep", "bwd_dq", "bwd_dkv", "coverage"]
 
 
 def sb_set_instrumentation(flag: int):

@@ -1,0 +1,266 @@
+// Budget controller around the attention path (paper section 4.1 and 4.2):
+//   sb_score_coverage   coverage curves C_s(k) of the routing scores (Eq. 4) on the GPU
+//   sb_perf_predict / sb_perf_align   the profiled latency table (Eq. 8-10), host
+//   sb_dst_tune         Algorithm 1 (anchor, Perf.align, coverage threshold p, Eq. 3/5/7), host
+//
+// Coverage.  For one query block i and one selection head the candidates are the earlier blocks
+// j < i; their scores are normalised by a softmax and sorted in descending order; a budget k keeps
+// the diagonal block and the k-1 best candidates, so the row covers pref_i[min(k-1, i)], the sum of
+// its min(k-1, i) largest shares (pref_i[i] = 1).  C_s(k) is the mean over the sequence's rows.
+// Two kernels, both deterministic (fixed summation order, no atomics):
+//   coverage_rows_kernel    one workgroup per query block (s, i): for every selection head in turn,
+//                           softmax + bitonic sort + prefix sum in LDS, summed over heads into
+//                           Pacc[s][i][m-1] = sum_hs pref_{hs,i}[m], m = 1..i
+//   coverage_reduce_kernel  one thread per (s, k): C_s(k) = (Hs*k + sum_{i>=k} Pacc[s][i][k-2]) / (Hs*n)
+//                           (the k rows i < k are fully covered)
+#include <math.h>
+
+#include "sb_internal.h"
+
+namespace sb {
+
+__device__ inline float block_reduce_256(float v, float* tmp, bool is_max) {
+  const int tid = threadIdx.x;
+  for (int off = 32; off > 0; off >>= 1) {
+    const float o = __shfl_xor(v, off, 64);
+    v = is_max ? fmaxf(v, o) : v + o;
+  }
+  __syncthreads();
+  if ((tid & 63) == 0) tmp[tid >> 6] = v;
+  __syncthreads();
+  float r = tmp[0];
+  for (int w = 1; w < 4; ++w) r = is_max ? fmaxf(r, tmp[w]) : r + tmp[w];
+  return r;  // the same value, combined in the same order, in every thread
+}
+
+__global__ __launch_bounds__(256) void coverage_rows_kernel(const float* __restrict__ scores, const int32_t* __restrict__ qb_off,
+                                                            const int64_t* __restrict__ sc_off, const int32_t* __restrict__ qb_seq,
+                                                            int Hs, float* __restrict__ pacc) {
+  extern __shared__ float smem[];  // keys[N], acc[N], tmp[260]
+  const int tid = threadIdx.x;
+  const int qb = blockIdx.x;
+  const int s = qb_seq[qb];
+  const int i = qb - qb_off[s];
+  const int n = qb_off[s + 1] - qb_off[s];
+  if (i == 0) return;  // no candidates: the row is fully covered at every budget
+  int N = 1;
+  while (N < i) N <<= 1;
+  float* keys = smem;
+  float* acc = smem + N;
+  float* tmp = smem + 2 * N;
+  for (int j = tid; j < i; j += 256) acc[j] = 0.f;
+  const int chunk = (N + 255) / 256;  // contiguous elements per thread in the prefix sum
+  for (int hs = 0; hs < Hs; ++hs) {
+    const float* row = scores + (int64_t)Hs * sc_off[s] + ((int64_t)hs * n + i) * n;
+    float mx = -INFINITY;
+    for (int j = tid; j < N; j += 256) {
+      const float x = j < i ? row[j] : -INFINITY;
+      keys[j] = x;
+      mx = fmaxf(mx, x);
+    }
+    mx = block_reduce_256(mx, tmp, true);
+    // bitonic sort, descending
+    for (int k2 = 2; k2 <= N; k2 <<= 1) {
+      for (int j2 = k2 >> 1; j2 > 0; j2 >>= 1) {
+        __syncthreads();
+        for (int t = tid; t < (N >> 1); t += 256) {
+          const int lo = ((t / j2) * 2 * j2) + (t % j2), hi = lo + j2;
+          const bool desc = (lo & k2) == 0;
+          const float a = keys[lo], b = keys[hi];
+          if (desc ? a < b : a > b) { keys[lo] = b; keys[hi] = a; }
+        }
+      }
+    }
+    __syncthreads();
+    // shares in sorted order, their total, and the running sum
+    float part = 0.f;
+    const int c0 = tid * chunk, c1 = min(c0 + chunk, N);
+    for (int j = c0; j < c1; ++j) {
+      const float e = j < i ? __expf(keys[j] - mx) : 0.f;
+      keys[j] = e;
+      part += e;
+    }
+    __syncthreads();
+    tmp[4 + tid] = part;
+    __syncthreads();
+    float before = 0.f, total = 0.f;  // serial over 256 partials: the same order in every thread
+    for (int t = 0; t < 256; ++t) {
+      if (t == tid) before = total;
+      total += tmp[4 + t];
+    }
+    const float inv = 1.0f / total;
+    float run = before;
+    for (int j = c0; j < c1; ++j) {
+      run += keys[j];
+      if (j < i) acc[j] += j == i - 1 ? 1.0f : run * inv;
+    }
+    __syncthreads();
+  }
+  float* out = pacc + sc_off[s] + (int64_t)i * n;
+  for (int j = tid; j < i; j += 256) out[j] = acc[j];
+}
+
+__global__ __launch_bounds__(256) void coverage_reduce_kernel(const float* __restrict__ pacc, const int32_t* __restrict__ qb_off,
+                                                              const int64_t* __restrict__ sc_off, const int32_t* __restrict__ qb_seq,
+                                                              int64_t NQB, int Hs, float* __restrict__ cov) {
+  const int64_t qb = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (qb >= NQB) return;
+  const int s = qb_seq[qb];
+  const int n = qb_off[s + 1] - qb_off[s];
+  const int k = (int)(qb - qb_off[s]) + 1;
+  double sum = (double)Hs * k;
+  if (k >= 2) {
+    const float* col = pacc + sc_off[s] + (k - 2);
+    for (int i = k; i < n; ++i) sum += (double)col[(int64_t)i * n];
+  }
+  cov[qb] = (float)(sum / ((double)Hs * n));
+}
+
+size_t coverage_ws_bytes(const Geo& g) {
+  return align_up(table_offsets(g).bytes) + align_up(sizeof(float) * (size_t)(g.scores_unit + 1));
+}
+
+// ---- latency table (host, double arithmetic)
+static void bracket(const float* grid, int n, double v, int* a, double* w) {
+  if (n == 1 || v <= (double)grid[0]) { *a = 0; *w = 0.0; return; }
+  if (v >= (double)grid[n - 1]) { *a = n - 2; *w = 1.0; return; }
+  int lo = 0;
+  while (lo + 1 < n && (double)grid[lo + 1] <= v) ++lo;  // last bucket edge <= v
+  *a = lo;
+  *w = (v - (double)grid[lo]) / ((double)grid[lo + 1] - (double)grid[lo]);
+}
+
+static int check_table(const sb_perf_table* t) {
+  if (!t || t->num_lengths < 1 || t->num_budgets < 1 || !t->lengths || !t->budgets || !t->latency) {
+    set_error("bad latency table");
+    return SB_ERR_INVALID_ARG;
+  }
+  for (int a = 1; a < t->num_lengths; ++a)
+    if (!(t->lengths[a] > t->lengths[a - 1])) { set_error("latency table: lengths must increase"); return SB_ERR_INVALID_ARG; }
+  for (int b = 1; b < t->num_budgets; ++b)
+    if (!(t->budgets[b] > t->budgets[b - 1])) { set_error("latency table: budgets must increase"); return SB_ERR_INVALID_ARG; }
+  return SB_OK;
+}
+
+static double predict(const sb_perf_table* t, double x, double k) {
+  int a, b;
+  double wa, wb;
+  bracket(t->lengths, t->num_lengths, x, &a, &wa);
+  bracket(t->budgets, t->num_budgets, k, &b, &wb);
+  const int a2 = a + 1 < t->num_lengths ? a + 1 : t->num_lengths - 1, b2 = b + 1 < t->num_budgets ? b + 1 : t->num_budgets - 1;
+  const int nk = t->num_budgets;
+  const double lo = (1.0 - wb) * (double)t->latency[a * nk + b] + wb * (double)t->latency[a * nk + b2];
+  const double hi = (1.0 - wb) * (double)t->latency[a2 * nk + b] + wb * (double)t->latency[a2 * nk + b2];
+  return (1.0 - wa) * lo + wa * hi;
+}
+
+static int align(const sb_perf_table* t, double x, double target, int kmax) {
+  int best = 1;
+  for (int k = 1; k <= kmax; ++k)
+    if (predict(t, x, (double)k) <= target) best = k;
+  return best;
+}
+
+}  // namespace sb
+
+using namespace sb;
+
+extern "C" {
+
+int sb_score_coverage(const sb_problem* p, const float* scores, float* coverage_out, void* ws, void* stream) {
+  Geo g;
+  int rc = make_geo(p, &g);
+  if (rc != SB_OK) return rc;
+  if (g.S == 0 || g.T == 0 || g.NQB == 0) return SB_OK;
+  if (!scores || !coverage_out || !ws) { set_error("null scores, coverage_out or ws"); return SB_ERR_INVALID_ARG; }
+  hipStream_t st = (hipStream_t)stream;
+  rc = launch_geom(g, p, ws, st);
+  if (rc != SB_OK) return rc;
+  Tables t = make_tables(g, p, ws);
+  float* pacc = (float*)((char*)ws + align_up(table_offsets(g).bytes));
+  int N = 1;
+  while (N < g.n_max) N <<= 1;
+  const size_t smem = sizeof(float) * (size_t)(2 * N + 264);
+  if (smem > 48 * 1024) {
+    static bool attr_set = false;
+    if (!attr_set) {
+      SB_CHECK_HIP(hipFuncSetAttribute((const void*)coverage_rows_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)(sizeof(float) * (2 * SB_MAX_BLOCKS_PER_SEQ + 264))));
+      attr_set = true;
+    }
+  }
+  KernelTimer kt(K_COVERAGE, st);
+  hipLaunchKernelGGL(coverage_rows_kernel, dim3((unsigned)g.NQB), dim3(256), smem, st, scores, t.qb_off, t.sc_off, t.qb_seq, g.Hs, pacc);
+  SB_LAUNCH_CHECK("coverage_rows_kernel");
+  hipLaunchKernelGGL(coverage_reduce_kernel, dim3((unsigned)((g.NQB + 255) / 256)), dim3(256), 0, st, pacc, t.qb_off, t.sc_off, t.qb_seq,
+                     g.NQB, g.Hs, coverage_out);
+  SB_LAUNCH_CHECK("coverage_reduce_kernel");
+  return SB_OK;
+}
+
+int sb_perf_predict(const sb_perf_table* t, double length, double budget, double* latency_out) {
+  int rc = check_table(t);
+  if (rc != SB_OK) return rc;
+  if (!latency_out) { set_error("null latency_out"); return SB_ERR_INVALID_ARG; }
+  *latency_out = predict(t, length, budget);
+  return SB_OK;
+}
+
+int sb_perf_align(const sb_perf_table* t, double length, double target_latency, int32_t max_budget, int32_t* budget_out) {
+  int rc = check_table(t);
+  if (rc != SB_OK) return rc;
+  if (!budget_out || max_budget < 1) { set_error("bad budget_out or max_budget"); return SB_ERR_INVALID_ARG; }
+  *budget_out = align(t, length, target_latency, max_budget);
+  return SB_OK;
+}
+
+int sb_dst_tune(const sb_problem* p, const float* coverage_host, const sb_perf_table* perf, int anchor, double threshold_p,
+                int32_t* topk_final_out, int32_t* topk_anchor_out, double* t_anchor_out) {
+  Geo g;
+  int rc = make_geo(p, &g);
+  if (rc != SB_OK) return rc;
+  if ((rc = check_table(perf)) != SB_OK) return rc;
+  if (anchor != SB_ANCHOR_MIN && anchor != SB_ANCHOR_MEAN && anchor != SB_ANCHOR_MAX) { set_error("bad anchor %d", anchor); return SB_ERR_INVALID_ARG; }
+  if (g.S > 0 && (!coverage_host || !topk_final_out)) { set_error("null coverage_host or topk_final_out"); return SB_ERR_INVALID_ARG; }
+  std::vector<int> n(g.S), kb(g.S);
+  std::vector<double> T;
+  for (int s = 0; s < g.S; ++s) {
+    const int64_t L = (int64_t)p->cu_seqlens_host[s + 1] - p->cu_seqlens_host[s];
+    n[s] = (int)((L + g.B - 1) / g.B);
+    const int cap = n[s] > 1 ? n[s] : 1;
+    kb[s] = p->topk_host[s] < cap ? p->topk_host[s] : cap;
+    if (n[s] > 0) T.push_back(predict(perf, (double)L, (double)kb[s]));
+  }
+  double Ta = 0.0;
+  if (!T.empty()) {
+    if (anchor == SB_ANCHOR_MEAN) {
+      double sum = 0.0;
+      for (double v : T) sum += v;
+      Ta = sum / (double)T.size();
+    } else {
+      Ta = T[0];
+      for (double v : T) Ta = anchor == SB_ANCHOR_MIN ? (v < Ta ? v : Ta) : (v > Ta ? v : Ta);
+    }
+  }
+  if (t_anchor_out) *t_anchor_out = Ta;
+  int64_t off = 0;
+  for (int s = 0; s < g.S; ++s) {
+    int kf = kb[s], ka = kb[s];
+    if (n[s] > 0) {
+      const int64_t L = (int64_t)p->cu_seqlens_host[s + 1] - p->cu_seqlens_host[s];
+      const float* C = coverage_host + off;
+      ka = align(perf, (double)L, Ta, n[s]);
+      kf = ka;
+      if ((double)C[kb[s] - 1] - (double)C[ka - 1] > threshold_p) {
+        for (int k = 1; k <= n[s]; ++k)
+          if ((double)C[kb[s] - 1] - (double)C[k - 1] <= threshold_p) { kf = k; break; }
+      }
+    }
+    topk_final_out[s] = kf;
+    if (topk_anchor_out) topk_anchor_out[s] = ka;
+    off += n[s];
+  }
+  return SB_OK;
+}
+
+}  // extern "C"

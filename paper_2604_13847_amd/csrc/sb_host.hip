@@ -252,6 +252,7 @@ int sb_get_layout(const sb_problem* p, sb_layout* out) {
   out->fwd_ws_bytes = (int64_t)fwd_ws_offsets(g).bytes;
   out->bwd_ws_bytes = (int64_t)bwd_ws_offsets(g).bytes;
   out->attended_pairs_per_head_sum = g.pairs_unit * g.Hq;
+  out->coverage_ws_bytes = (int64_t)coverage_ws_bytes(g);
   return SB_OK;
 }
 

@@ -88,3 +88,53 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(sb, "LIB_PATH", "/nonexistent/libsparsebal.so")
     with pytest.raises(sb.SparseBalError):
         sb.sb_version()
+
+
+# ---------------------------------------------------------------- budget controller, host side
+def _random_table(rng, nx, nk):
+    xs = np.cumsum(rng.integers(200, 5000, size=nx)).astype(np.float32)
+    ks = np.cumsum(rng.integers(1, 12, size=nk)).astype(np.float32)
+    lat = (np.outer(xs, ks) * 1e-4 * rng.uniform(0.7, 1.3, size=(nx, nk))).astype(np.float32)
+    return xs, ks, lat
+
+
+def test_latency_table_predict_and_align_match_the_checker():
+    from oracle import dst_oracle as dst
+    rng = np.random.default_rng(11)
+    for nx, nk in ((1, 1), (1, 4), (3, 1), (5, 6)):
+        xs, ks, lat = _random_table(rng, nx, nk)
+        tab = sb.PerfTable(xs, ks, lat)
+        for _ in range(40):
+            x = float(rng.uniform(0.5 * xs[0], 1.2 * xs[-1])); k = float(rng.integers(1, int(ks[-1]) + 4))
+            assert sb.sb_perf_predict(tab, x, k) == dst.perf_predict(xs, ks, lat, x, k)
+            T = float(rng.uniform(0.0, 1.2 * lat.max()))
+            assert sb.sb_perf_align(tab, x, T, 40) == dst.perf_align(xs, ks, lat, x, T, 40)
+        for a in range(nx):      # exact at the grid points
+            for b in range(nk):
+                assert sb.sb_perf_predict(tab, float(xs[a]), float(ks[b])) == float(lat[a, b])
+    with pytest.raises(sb.SparseBalError):
+        sb.sb_perf_predict(sb.PerfTable([2.0, 1.0], [1.0], [[1.0], [2.0]]), 1.0, 1.0)
+
+
+@pytest.mark.parametrize("anchor", [0, 1, 2])
+def test_dst_tune_matches_the_checker(anchor):
+    from oracle import dst_oracle as dst
+    rng = np.random.default_rng(12 + anchor)
+    lens = [700, 64, 0, 5000, 12000, 1, 2300]
+    cu = synth.cu_from_lengths(lens)
+    nblk = [(L + 63) // 64 for L in lens]
+    Hs = 2
+    blocks, off = [], [0]
+    for n in nblk:
+        blocks.append(rng.normal(size=Hs * n * n) * 2.5)
+        off.append(off[-1] + Hs * n * n)
+    cov = dst.coverage_curves(nblk, Hs, np.concatenate(blocks), off).astype(np.float32)
+    qb = np.concatenate([[0], np.cumsum(nblk)]).astype(int)
+    xs, ks, lat = _random_table(rng, 4, 5)
+    tab = sb.PerfTable(xs, ks, lat)
+    kbase = [3, 1, 1, 20, 30, 1, 40]   # the last one is clamped to its 36 blocks
+    pb = sb.Problem(cu, kbase, 4, 2, 64)
+    for p in (0.0, 0.02, 0.1, 0.3, 1.0):
+        kf, ka, ta = sb.sb_dst_tune(pb, cov, tab, anchor, p)
+        rf, ra, rt = dst.dst_budgets(p, anchor, lens, nblk, kbase, cov, qb, xs, ks, lat)
+        assert np.array_equal(kf, rf) and np.array_equal(ka, ra) and ta == rt
