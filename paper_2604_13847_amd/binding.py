@@ -197,6 +197,14 @@ class PerfTable:
     def ref(self):
         return C.byref(self.c)
 
+    @classmethod
+    def from_json(cls, path):
+        """A table written by paper_2604_13847_amd/profile_latency.py."""
+        import json
+        with open(path) as f:
+            j = json.load(f)
+        return cls(j["lengths"], j["budgets"], j["latency_ms"])
+
 
 def sb_perf_predict(tab: PerfTable, length, budget) -> float:
     out = C.c_double()

@@ -8,11 +8,11 @@
 // the diagonal block and the k-1 best candidates, so the row covers pref_i[min(k-1, i)], the sum of
 // its min(k-1, i) largest shares (pref_i[i] = 1).  C_s(k) is the mean over the sequence's rows.
 // Two kernels, both deterministic (fixed summation order, no atomics):
-//   coverage_rows_kernel    one workgroup per query block (s, i): for every selection head in turn,
+//   coverage_rows_kernel    one workgroup per query block (s, i) and group of selection heads: for every head in turn,
 //                           softmax + bitonic sort + prefix sum in LDS, summed over heads into
 //                           Pacc[s][i][m-1] = sum_hs pref_{hs,i}[m], m = 1..i
-//   coverage_reduce_kernel  one thread per (s, k): C_s(k) = (Hs*k + sum_{i>=k} Pacc[s][i][k-2]) / (Hs*n)
-//                           (the k rows i < k are fully covered)
+//   coverage_partial_kernel / coverage_reduce_kernel   one thread per (s, k): column sums of Pacc over slabs of 32 query
+//                           blocks, then C_s(k) = (Hs*k + sum_{i>=k} Pacc[s][i][k-2]) / (Hs*n) (the k rows i < k are fully covered)
 #include <math.h>
 
 #include "sb_internal.h"
@@ -35,7 +35,7 @@ __device__ inline float block_reduce_256(float v, float* tmp, bool is_max) {
 
 __global__ __launch_bounds__(256) void coverage_rows_kernel(const float* __restrict__ scores, const int32_t* __restrict__ qb_off,
                                                             const int64_t* __restrict__ sc_off, const int32_t* __restrict__ qb_seq,
-                                                            int Hs, float* __restrict__ pacc) {
+                                                            int Hs, int64_t slab, float* __restrict__ pacc) {
   extern __shared__ float smem[];  // keys[N], acc[N], tmp[260]
   const int tid = threadIdx.x;
   const int qb = blockIdx.x;
@@ -50,7 +50,9 @@ __global__ __launch_bounds__(256) void coverage_rows_kernel(const float* __restr
   float* tmp = smem + 2 * N;
   for (int j = tid; j < i; j += 256) acc[j] = 0.f;
   const int chunk = (N + 255) / 256;  // contiguous elements per thread in the prefix sum
-  for (int hs = 0; hs < Hs; ++hs) {
+  const int hpg = (Hs + (int)gridDim.y - 1) / (int)gridDim.y;  // selection heads per group
+  const int hs0 = blockIdx.y * hpg, hs1 = min(Hs, hs0 + hpg);
+  for (int hs = hs0; hs < hs1; ++hs) {
     const float* row = scores + (int64_t)Hs * sc_off[s] + ((int64_t)hs * n + i) * n;
     float mx = -INFINITY;
     for (int j = tid; j < N; j += 256) {
@@ -80,13 +82,20 @@ __global__ __launch_bounds__(256) void coverage_rows_kernel(const float* __restr
       keys[j] = e;
       part += e;
     }
+    // exclusive prefix of the 256 partial sums: shuffle scan inside each wavefront, then the four wavefront totals
+    float incl = part;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const float up = __shfl_up(incl, off, 64);
+      if ((tid & 63) >= off) incl += up;
+    }
     __syncthreads();
-    tmp[4 + tid] = part;
+    if ((tid & 63) == 63) tmp[tid >> 6] = incl;
     __syncthreads();
-    float before = 0.f, total = 0.f;  // serial over 256 partials: the same order in every thread
-    for (int t = 0; t < 256; ++t) {
-      if (t == tid) before = total;
-      total += tmp[4 + t];
+    float before = incl - part, total = 0.f;
+    for (int w = 0; w < 4; ++w) {
+      if (w < (tid >> 6)) before += tmp[w];
+      total += tmp[w];
     }
     const float inv = 1.0f / total;
     float run = before;
@@ -96,28 +105,52 @@ __global__ __launch_bounds__(256) void coverage_rows_kernel(const float* __restr
     }
     __syncthreads();
   }
-  float* out = pacc + sc_off[s] + (int64_t)i * n;
+  float* out = pacc + (int64_t)blockIdx.y * slab + sc_off[s] + (int64_t)i * n;
   for (int j = tid; j < i; j += 256) out[j] = acc[j];
 }
 
-__global__ __launch_bounds__(256) void coverage_reduce_kernel(const float* __restrict__ pacc, const int32_t* __restrict__ qb_off,
-                                                              const int64_t* __restrict__ sc_off, const int32_t* __restrict__ qb_seq,
-                                                              int64_t NQB, int Hs, float* __restrict__ cov) {
+// partial column sums over slabs of kCovSlab query blocks: part[y][qb] = sum over head groups and rows i of slab y, i >= k
+constexpr int kCovSlab = 32;
+__global__ __launch_bounds__(256) void coverage_partial_kernel(const float* __restrict__ pacc, const int32_t* __restrict__ qb_off,
+                                                               const int64_t* __restrict__ sc_off, const int32_t* __restrict__ qb_seq,
+                                                               int64_t NQB, int groups, int64_t slab, float* __restrict__ part) {
   const int64_t qb = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (qb >= NQB) return;
   const int s = qb_seq[qb];
   const int n = qb_off[s + 1] - qb_off[s];
   const int k = (int)(qb - qb_off[s]) + 1;
-  double sum = (double)Hs * k;
+  const int i0 = max(k, (int)blockIdx.y * kCovSlab), i1 = min(n, ((int)blockIdx.y + 1) * kCovSlab);
+  float sum = 0.f;
   if (k >= 2) {
-    const float* col = pacc + sc_off[s] + (k - 2);
-    for (int i = k; i < n; ++i) sum += (double)col[(int64_t)i * n];
+    for (int gidx = 0; gidx < groups; ++gidx) {
+      const float* col = pacc + (int64_t)gidx * slab + sc_off[s] + (k - 2);
+      for (int i = i0; i < i1; ++i) sum += col[(int64_t)i * n];
+    }
   }
+  part[(int64_t)blockIdx.y * NQB + qb] = sum;
+}
+
+__global__ __launch_bounds__(256) void coverage_reduce_kernel(const float* __restrict__ part, const int32_t* __restrict__ qb_off,
+                                                              const int32_t* __restrict__ qb_seq, int64_t NQB, int Hs,
+                                                              float* __restrict__ cov) {
+  const int64_t qb = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (qb >= NQB) return;
+  const int s = qb_seq[qb];
+  const int n = qb_off[s + 1] - qb_off[s];
+  const int k = (int)(qb - qb_off[s]) + 1;
+  double sum = (double)Hs * k;  // the k rows i < k are fully covered
+  for (int y = k / kCovSlab; y * kCovSlab < n; ++y) sum += (double)part[(int64_t)y * NQB + qb];
   cov[qb] = (float)(sum / ((double)Hs * n));
 }
 
+// selection heads are processed in up to kCovGroups groups by separate workgroups (one slab of partial sums each)
+constexpr int kCovGroups = 4;
+static int coverage_groups(const Geo& g) { return g.Hs < kCovGroups ? g.Hs : kCovGroups; }
+static size_t coverage_slab(const Geo& g) { return align_up(sizeof(float) * (size_t)(g.scores_unit + 1)) / sizeof(float); }
+static int coverage_row_slabs(const Geo& g) { return (g.n_max + kCovSlab - 1) / kCovSlab; }
 size_t coverage_ws_bytes(const Geo& g) {
-  return align_up(table_offsets(g).bytes) + align_up(sizeof(float) * (size_t)(g.scores_unit + 1));
+  return align_up(table_offsets(g).bytes) + sizeof(float) * coverage_slab(g) * (size_t)coverage_groups(g) +
+         align_up(sizeof(float) * (size_t)(coverage_row_slabs(g) * g.NQB + 1));
 }
 
 // ---- latency table (host, double arithmetic)
@@ -190,10 +223,17 @@ int sb_score_coverage(const sb_problem* p, const float* scores, float* coverage_
     }
   }
   KernelTimer kt(K_COVERAGE, st);
-  hipLaunchKernelGGL(coverage_rows_kernel, dim3((unsigned)g.NQB), dim3(256), smem, st, scores, t.qb_off, t.sc_off, t.qb_seq, g.Hs, pacc);
+  const int groups = coverage_groups(g);
+  const int64_t slab = (int64_t)coverage_slab(g);
+  hipLaunchKernelGGL(coverage_rows_kernel, dim3((unsigned)g.NQB, (unsigned)groups), dim3(256), smem, st, scores, t.qb_off, t.sc_off,
+                     t.qb_seq, g.Hs, slab, pacc);
   SB_LAUNCH_CHECK("coverage_rows_kernel");
-  hipLaunchKernelGGL(coverage_reduce_kernel, dim3((unsigned)((g.NQB + 255) / 256)), dim3(256), 0, st, pacc, t.qb_off, t.sc_off, t.qb_seq,
-                     g.NQB, g.Hs, coverage_out);
+  float* part = pacc + slab * groups;
+  hipLaunchKernelGGL(coverage_partial_kernel, dim3((unsigned)((g.NQB + 255) / 256), (unsigned)coverage_row_slabs(g)), dim3(256), 0, st, pacc,
+                     t.qb_off, t.sc_off, t.qb_seq, g.NQB, groups, slab, part);
+  SB_LAUNCH_CHECK("coverage_partial_kernel");
+  hipLaunchKernelGGL(coverage_reduce_kernel, dim3((unsigned)((g.NQB + 255) / 256)), dim3(256), 0, st, part, t.qb_off, t.qb_seq, g.NQB, g.Hs,
+                     coverage_out);
   SB_LAUNCH_CHECK("coverage_reduce_kernel");
   return SB_OK;
 }

@@ -1,0 +1,86 @@
+#!/usr/bin/env python3
+"""Fill the latency table M[x, k] of the budget controller (paper section 4.2, Eq. 10) by profiling
+this library's own attention path on the GPU it runs on: for every (sequence length x, budget k) one
+packed sequence is pushed through scores -> selection -> plan -> forward -> backward and the time of
+the attention calls (forward + backward, the part the budget changes) is recorded.
+
+usage: python -m paper_2604_13847_amd.profile_latency [--out table.json] [--heads 32 8] [--dim 128]
+The JSON holds {"lengths": [...], "budgets": [...], "latency_ms": [[...]], "heads": [Hq, Hkv], "head_dim": D}.
+"""
+import argparse
+import json
+import os
+import sys
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+LENGTHS = [1024, 2048, 4096, 8192, 16384, 32768, 65536]
+BUDGETS = [1, 2, 4, 8, 16, 32, 64, 128]
+
+
+def measure(sb, torch, synth, L, k, Hq, Hkv, D, reps=5):
+    dev = "cuda:0"
+    w = synth.Workload("probe", [L], Hq, Hkv, D, topk=[k], seed=0)
+    pb = sb.Problem(w.cu, w.topk, Hq, Hkv, D, 64, device=dev)
+    g = torch.Generator(device=dev).manual_seed(L + k)
+    q, do = (torch.randn((L, Hq, D), device=dev, generator=g).to(torch.bfloat16) for _ in range(2))
+    kk, v = (torch.randn((L, Hkv, D), device=dev, generator=g).to(torch.bfloat16) for _ in range(2))
+    scores = sb.sb_block_scores(pb, q, kk)
+    rowptr, idx = sb.sb_select_topk(pb, scores)
+    plan = sb.sb_plan_worklist(pb, rowptr, idx)
+    lay = pb.layout
+    ws_f = torch.empty(max(lay.fwd_ws_bytes, 256), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(max(lay.bwd_ws_bytes, 256), dtype=torch.uint8, device=dev)
+    o, lse = sb.sb_sparse_attn_fwd(pb, q, kk, v, rowptr, idx, plan, ws=ws_f)
+    dq, dk, dv = sb.sb_sparse_attn_bwd(pb, q, kk, v, o, lse, do, rowptr, idx, plan, ws=ws_b)
+    times = []
+    for _ in range(reps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        sb.sb_sparse_attn_fwd(pb, q, kk, v, rowptr, idx, plan, o=o, lse=lse, ws=ws_f)
+        sb.sb_sparse_attn_bwd(pb, q, kk, v, o, lse, do, rowptr, idx, plan, dq=dq, dk=dk, dv=dv, ws=ws_b)
+        b.record()
+        b.synchronize()
+        times.append(a.elapsed_time(b))
+    return float(np.median(times))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--out", default=os.path.join(ROOT, "gpurun_out", "latency_table.json"))
+    ap.add_argument("--heads", type=int, nargs=2, default=[32, 8])
+    ap.add_argument("--dim", type=int, default=128)
+    ap.add_argument("--check", action="store_true", help="also measure points between the buckets and report the prediction error")
+    args = ap.parse_args()
+    import torch
+    from paper_2604_13847_amd import binding as sb
+    from paper_2604_13847_amd import synth
+    assert torch.cuda.is_available(), "profiling needs a GPU"
+    Hq, Hkv = args.heads
+    lat = np.zeros((len(LENGTHS), len(BUDGETS)), dtype=np.float32)
+    for a, L in enumerate(LENGTHS):
+        for b, k in enumerate(BUDGETS):
+            lat[a, b] = measure(sb, torch, synth, L, k, Hq, Hkv, args.dim)
+        print(f"L={L:6d} " + " ".join(f"{x:8.3f}" for x in lat[a]), flush=True)
+    out = {"lengths": LENGTHS, "budgets": BUDGETS, "latency_ms": [[round(float(x), 4) for x in row] for row in lat],
+           "heads": [Hq, Hkv], "head_dim": args.dim, "what": "median ms of sb_sparse_attn_fwd + sb_sparse_attn_bwd on one packed sequence"}
+    if args.check:
+        tab = sb.PerfTable(LENGTHS, BUDGETS, lat)
+        errs = []
+        for L, k in ((1536, 3), (3000, 6), (6000, 12), (12000, 24), (24000, 48), (50000, 20), (40000, 96)):
+            got, pred = measure(sb, torch, synth, L, k, Hq, Hkv, args.dim), sb.sb_perf_predict(tab, L, k)
+            errs.append({"length": L, "budget": k, "measured_ms": round(got, 4), "predicted_ms": round(pred, 4), "rel_err": round(pred / got - 1.0, 4)})
+            print(errs[-1], flush=True)
+        out["check"] = errs
+    os.makedirs(os.path.dirname(args.out), exist_ok=True)
+    with open(args.out, "w") as f:
+        json.dump(out, f, indent=1)
+    print("wrote", args.out)
+
+
+if __name__ == "__main__":
+    main()

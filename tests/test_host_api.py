@@ -138,3 +138,12 @@ def test_dst_tune_matches_the_checker(anchor):
         kf, ka, ta = sb.sb_dst_tune(pb, cov, tab, anchor, p)
         rf, ra, rt = dst.dst_budgets(p, anchor, lens, nblk, kbase, cov, qb, xs, ks, lat)
         assert np.array_equal(kf, rf) and np.array_equal(ka, ra) and ta == rt
+
+
+def test_shipped_latency_table_loads_and_aligns():
+    tab = sb.PerfTable.from_json(os.path.join(ROOT, "paper_2604_13847_amd", "perf_tables", "mi355x_hq32_hkv8_d128.json"))
+    assert np.all(np.diff(tab.lengths) > 0) and np.all(np.diff(tab.budgets) > 0) and np.all(tab.latency > 0)
+    # the profiled latency grows with the length at every budget; a longer sequence gets a smaller budget for the same target
+    assert np.all(np.diff(tab.latency, axis=0) > 0)
+    t = sb.sb_perf_predict(tab, 16384, 32)
+    assert sb.sb_perf_align(tab, 16384, t, 256) >= 32 > sb.sb_perf_align(tab, 32768, t, 512)
