@@ -180,6 +180,30 @@ int sb_perf_align(const sb_perf_table *t, double length, double target_latency, 
 int sb_dst_tune(const sb_problem *p, const float *coverage_host, const sb_perf_table *perf, int anchor,
                 double threshold_p, int32_t *topk_final_out, int32_t *topk_anchor_out, double *t_anchor_out);
 
+/* ---- sparsity-aware batching (paper section 4.3, Algorithm 2); host only, CPU side of the data loader ----
+ *
+ * Sparsity predictor Spar: for each sequence-length bin b (bin_edges[b] <= L < bin_edges[b+1], lengths
+ * outside clamp to the first / last bin) an exponential moving average of the final budgets the
+ * tuning step produced: ema[b] <- decay*ema[b] + (1-decay)*k per sample, in order; the first sample of
+ * a bin initialises it (seen[b] = 1).  sb_spar_predict returns ema[b], or k_base while the bin has
+ * seen nothing.  ema: [num_bins] float, seen: [num_bins] bytes, bin_edges: [num_bins+1]; caller-owned. */
+int sb_spar_update(float *ema, uint8_t *seen, const float *bin_edges, int32_t num_bins, double decay,
+                   const int32_t *lengths, const int32_t *k_final, int32_t n);
+int sb_spar_predict(const float *ema, const uint8_t *seen, const float *bin_edges, int32_t num_bins,
+                    int32_t length, double k_base, double *k_out);
+
+/* `bin_packing`: balanced partition of n weights into num_bins bins by the longest-first greedy
+ * (decreasing weight, ties to the lower index; each to the least loaded bin, ties to the lower bin).
+ * bin_of_out[i] is the bin of sample i.  Bin sizes are not constrained. */
+int sb_balanced_partition(const double *weights, int32_t n, int32_t num_bins, int32_t *bin_of_out);
+
+/* Algorithm 2: W[i] = Perf.predict(lengths[i], k_pred[i]); samples are split over dp_size DP ranks, then
+ * the samples of dp_rank over num_microbatches micro-batches (= gbs / (mbs * N)).  weights_out (nullable),
+ * dp_bin_out, mb_bin_out: [n]; mb_bin_out is -1 for the samples of other ranks. */
+int sb_sab_batches(const sb_perf_table *perf, const int32_t *lengths, const double *k_pred, int32_t n,
+                   int32_t dp_size, int32_t dp_rank, int32_t num_microbatches, double *weights_out,
+                   int32_t *dp_bin_out, int32_t *mb_bin_out);
+
 /* Instrumentation (measurement only; off by default).  `flag` is a bit set:
  *   SB_INSTR_CU_BUSY  the attention kernels add, for every workgroup, its run time in ticks of the
  *                     100 MHz constant clock to a per-compute-unit slot inside `ws`; sb_read_cu_busy

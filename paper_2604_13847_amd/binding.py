@@ -22,6 +22,7 @@ SB_CU_SLOTS = 512
 
 EXPORTS = ["sb_get_layout", "sb_keep_ratio_to_topk", "sb_sel_rowptr_host", "sb_block_scores", "sb_select_topk",
            "sb_plan_worklist", "sb_sparse_attn_fwd", "sb_sparse_attn_bwd", "sb_score_coverage", "sb_perf_predict", "sb_perf_align", "sb_dst_tune",
+           "sb_spar_update", "sb_spar_predict", "sb_balanced_partition", "sb_sab_batches",
            "sb_set_instrumentation", "sb_read_cu_busy", "sb_read_kernel_times",
            "sb_last_error", "sb_version"]
 
@@ -225,6 +226,42 @@ def sb_dst_tune(pb: Problem, coverage_host, tab: PerfTable, anchor, threshold_p)
     ta = C.c_double()
     _check(lib().sb_dst_tune(pb.ref(), _ptr(cov), tab.ref(), int(anchor), C.c_double(threshold_p), _ptr(kf), _ptr(ka), C.byref(ta)))
     return kf[: pb.S], ka[: pb.S], ta.value
+
+
+class SparsityPredictor:
+    """Spar of Algorithm 2: per length bin, a moving average of the budgets the tuning step produced."""
+
+    def __init__(self, bin_edges, decay=0.9):
+        self.edges = np.ascontiguousarray(bin_edges, dtype=np.float32)
+        self.nb = len(self.edges) - 1
+        self.ema = np.zeros(self.nb, dtype=np.float32)
+        self.seen = np.zeros(self.nb, dtype=np.uint8)
+        self.decay = float(decay)
+
+    def update(self, lengths, k_final):
+        L, k = np.ascontiguousarray(lengths, dtype=np.int32), np.ascontiguousarray(k_final, dtype=np.int32)
+        _check(lib().sb_spar_update(_ptr(self.ema), _ptr(self.seen), _ptr(self.edges), self.nb, C.c_double(self.decay), _ptr(L), _ptr(k), len(L)))
+
+    def predict(self, length, k_base) -> float:
+        out = C.c_double()
+        _check(lib().sb_spar_predict(_ptr(self.ema), _ptr(self.seen), _ptr(self.edges), self.nb, int(length), C.c_double(k_base), C.byref(out)))
+        return out.value
+
+
+def sb_balanced_partition(weights, num_bins) -> np.ndarray:
+    w = np.ascontiguousarray(weights, dtype=np.float64)
+    out = np.zeros(max(len(w), 1), dtype=np.int32)
+    _check(lib().sb_balanced_partition(_ptr(w), len(w), int(num_bins), _ptr(out)))
+    return out[: len(w)]
+
+
+def sb_sab_batches(tab: PerfTable, lengths, k_pred, dp_size, dp_rank, num_microbatches):
+    """Algorithm 2.  Returns (weights, dp_bin_of, mb_bin_of)."""
+    L, k = np.ascontiguousarray(lengths, dtype=np.int32), np.ascontiguousarray(k_pred, dtype=np.float64)
+    n = len(L)
+    w, dp, mb = np.zeros(max(n, 1)), np.zeros(max(n, 1), dtype=np.int32), np.zeros(max(n, 1), dtype=np.int32)
+    _check(lib().sb_sab_batches(tab.ref(), _ptr(L), _ptr(k), n, int(dp_size), int(dp_rank), int(num_microbatches), _ptr(w), _ptr(dp), _ptr(mb)))
+    return w[:n], dp[:n], mb[:n]
 
 
 SB_INSTR_CU_BUSY, SB_INSTR_KERNEL_EVENTS = 1, 2

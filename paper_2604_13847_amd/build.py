@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsparsebal.so")
-SOURCES = ["sb_host.hip", "sb_scores.hip", "sb_topk.hip", "sb_plan.hip", "sb_attn_fwd.hip", "sb_attn_bwd.hip", "sb_coverage.hip"]
+SOURCES = ["sb_host.hip", "sb_scores.hip", "sb_topk.hip", "sb_plan.hip", "sb_attn_fwd.hip", "sb_attn_bwd.hip", "sb_coverage.hip", "sb_sab.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-variable", "-Wno-inline-asm", "-Wno-pass-failed", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 

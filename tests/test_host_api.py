@@ -147,3 +147,38 @@ def test_shipped_latency_table_loads_and_aligns():
     assert np.all(np.diff(tab.latency, axis=0) > 0)
     t = sb.sb_perf_predict(tab, 16384, 32)
     assert sb.sb_perf_align(tab, 16384, t, 256) >= 32 > sb.sb_perf_align(tab, 32768, t, 512)
+
+
+# ---------------------------------------------------------------- sparsity-aware batching, host side
+def test_sab_matches_the_checker_and_balances_the_length_mix():
+    from oracle import dst_oracle as dst
+    from oracle import sab_oracle as sab
+    rng = np.random.default_rng(21)
+    tab = sb.PerfTable.from_json(os.path.join(ROOT, "paper_2604_13847_amd", "perf_tables", "mi355x_hq32_hkv8_d128.json"))
+    xs, ks, lat = tab.lengths, tab.budgets, tab.latency
+    lens = np.array(synth.mixed_lengths(3, 64 * 4096, short=(512, 4096), long=(8192, 32768)), dtype=np.int32)   # the 60/40 length mix
+    n = len(lens)
+    # sparsity predictor: moving average per length bin, exact against the checker
+    edges = [0, 2048, 8192, 16384, 1 << 30]
+    spar = sb.SparsityPredictor(edges, decay=0.8)
+    ema, seen = np.zeros(4), np.zeros(4, dtype=bool)
+    for step in range(3):
+        kfin = rng.integers(1, 64, size=n)
+        spar.update(lens, kfin)
+        for L, k in zip(lens, kfin):      # the library keeps the running value in float: mirror its rounding per sample
+            b = sab.length_bin(edges, L)
+            ema[b] = float(k) if not seen[b] else float(np.float32(0.8 * ema[b] + (1.0 - 0.8) * float(k)))
+            seen[b] = True
+    kpred = np.array([spar.predict(int(L), 16.0) for L in lens])
+    assert np.array_equal(kpred, np.array([sab.spar_predict(ema, seen, edges, L, 16.0) for L in lens]))
+    assert sb.SparsityPredictor(edges).predict(5000, 12.0) == 12.0
+    # weights and the two-level partition, exact
+    for rank in range(4):
+        w, dp, mb = sb.sb_sab_batches(tab, lens, kpred, 4, rank, 2)
+        wr = sab.sab_weights(xs, ks, lat, lens, kpred)
+        rdp, rmb = sab.sab_batches(wr, 4, rank, 2)
+        assert np.array_equal(w, wr) and np.array_equal(dp, rdp) and np.array_equal(mb, rmb)
+    assert np.array_equal(sb.sb_balanced_partition(wr, 7), sab.balanced_partition(wr, 7))
+    # Eq. 11 on the synthetic mix: latency-weighted bins are better balanced (in predicted latency) than length-weighted ones
+    by_len = sab.balanced_partition(lens.astype(np.float64), 4)
+    assert sab.imbalance(wr, dp, 4) <= sab.imbalance(wr, by_len, 4) + 1e-12
