@@ -674,7 +674,7 @@ extern "C" int sb_sparse_attn_bwd(const sb_problem* p, const void* q, const void
   P.out_f32 = f32;
   P.cu_busy = nullptr;
   if (g_instrument & 1) {
-    SB_CHECK_HIP(hipMemsetAsync(wb + wo.cu_busy, 0, sizeof(uint64_t) * SB_CU_SLOTS, st));
+    if ((rc = fill_zero(wb + wo.cu_busy, sizeof(uint64_t) * SB_CU_SLOTS, st)) != SB_OK) return rc;
     P.cu_busy = (unsigned long long*)(wb + wo.cu_busy);
   }
   const int64_t rows = (int64_t)g.T * g.Hq;

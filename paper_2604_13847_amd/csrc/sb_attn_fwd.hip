@@ -395,7 +395,7 @@ extern "C" int sb_sparse_attn_fwd(const sb_problem* p, const void* q, const void
   P.out_f32 = g.dtype == SB_F32;
   P.cu_busy = nullptr;
   if (g_instrument & 1) {
-    SB_CHECK_HIP(hipMemsetAsync(wb + wo.cu_busy, 0, sizeof(uint64_t) * SB_CU_SLOTS, st));
+    if ((rc = fill_zero(wb + wo.cu_busy, sizeof(uint64_t) * SB_CU_SLOTS, st)) != SB_OK) return rc;
     P.cu_busy = (unsigned long long*)(wb + wo.cu_busy);
   }
   const int heads = g.mode == SB_SELECT_PER_QHEAD ? 1 : g.G;  // query heads that share a work item

@@ -226,6 +226,19 @@ int launch_geom(const Geo& g, const sb_problem* p, void* base, hipStream_t st) {
   return SB_OK;
 }
 
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* __restrict__ dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = 0u;
+}
+
+int fill_zero(void* dst, size_t bytes, hipStream_t st) {
+  const size_t n = bytes / 4;
+  if (n == 0) return SB_OK;
+  const size_t blocks = (n + 255) / 256;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, st, (uint32_t*)dst, n);
+  SB_LAUNCH_CHECK("fill_zero_kernel");
+  return SB_OK;
+}
+
 }  // namespace sb
 
 using namespace sb;

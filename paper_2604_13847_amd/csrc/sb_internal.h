@@ -118,6 +118,10 @@ WsOffsets bwd_ws_offsets(const Geo& g);
 size_t scores_ws_bytes(const Geo& g);
 size_t coverage_ws_bytes(const Geo& g);
 
+// Zero `bytes` (a multiple of 4) at `dst` with a small kernel on `st`: unlike a memset node this is safe to record
+// into a HIP graph.
+int fill_zero(void* dst, size_t bytes, hipStream_t st);
+
 extern int g_instrument;  // bit 0: per-CU busy ticks, bit 1: HIP events around each kernel
 
 // HIP-event bracket around one kernel launch on its own stream (only when bit 1 is set).

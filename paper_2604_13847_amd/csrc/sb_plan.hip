@@ -137,7 +137,7 @@ extern "C" int sb_plan_worklist(const sb_problem* p, const int32_t* sel_rowptr, 
   const int64_t rows = (int64_t)g.Hs * g.NQB, ncol = (int64_t)g.Hkv * g.NQB;
   KernelTimer kt(K_PLAN, st);
   // colcost, work_bwd, bins and bitmap are adjacent: clear colcost, bins and bitmap
-  SB_CHECK_HIP(hipMemsetAsync(colcost, 0, po.bytes - po.colcost, st));
+  if ((rc = fill_zero(colcost, po.bytes - po.colcost, st)) != SB_OK) return rc;
   hipLaunchKernelGGL(plan_fwd_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, t.qb_off, t.kclamp, t.qb_seq,
                      t.cu, sel_rowptr, g.S, g.NQB, g.Hs, g.Hkv, g.G, g.mode, work_fwd, (WorkItem*)(base + po.items));
   SB_LAUNCH_CHECK("plan_fwd_kernel");

@@ -130,8 +130,7 @@ extern "C" int sb_select_topk(const sb_problem* p, const float* scores, int32_t*
   if (!sel_rowptr_out) { set_error("null sel_rowptr_out"); return SB_ERR_INVALID_ARG; }
   hipStream_t st = (hipStream_t)stream;
   if (g.S == 0 || g.T == 0 || g.NQB == 0) {
-    SB_CHECK_HIP(hipMemsetAsync(sel_rowptr_out, 0, sizeof(int32_t), st));
-    return SB_OK;
+    return fill_zero(sel_rowptr_out, sizeof(int32_t), st);
   }
   if (!scores || !sel_idx_out || !ws) { set_error("null scores, sel_idx_out or ws"); return SB_ERR_INVALID_ARG; }
   rc = launch_geom(g, p, ws, st);
