@@ -636,16 +636,17 @@ using namespace sb;
 extern "C" int sb_sparse_attn_bwd(const sb_problem* p, const void* q, const void* k, const void* v, const void* o,
                                   const float* lse, const void* d_o, const int32_t* sel_rowptr, const int32_t* sel_idx,
                                   const void* plan, void* dq, void* dk, void* dv, void* ws, void* stream) {
-  Geo g;
-  int rc = make_geo(p, &g);
+  Geo gb;
+  int rc = make_geo(p, &gb);
   if (rc != SB_OK) return rc;
-  if (g.S == 0 || g.T == 0 || g.NQB == 0) return SB_OK;
+  if (gb.S == 0 || gb.T == 0 || gb.NQB == 0) return SB_OK;
+  const Geo g = tile_geo(gb);  // the kernels work on 64-row tiles; for larger selection blocks the plan holds the tile-level selection
   if (!q || !k || !v || !o || !lse || !d_o || !sel_rowptr || !sel_idx || !plan || !dq || !dk || !dv || !ws) {
     set_error("null argument");
     return SB_ERR_INVALID_ARG;
   }
   hipStream_t st = (hipStream_t)stream;
-  PlanOffsets po = plan_offsets(g);
+  PlanOffsets po = plan_offsets(gb);
   WsOffsets wo = bwd_ws_offsets(g);
   const char* pb = (const char*)plan;
   char* wb = (char*)ws;
@@ -665,7 +666,8 @@ extern "C" int sb_sparse_attn_bwd(const sb_problem* p, const void* q, const void
   float* drow = (float*)(wb + wo.drow);
   float* lse2 = (float*)(wb + wo.lse2);
   P.lse = (float*)lse; P.drow = drow; P.lse2 = lse2; P.dq = dq; P.dk = dk; P.dv = dv;
-  P.rowptr = sel_rowptr; P.idx = sel_idx;
+  P.rowptr = gb.r == 1 ? sel_rowptr : (const int32_t*)(pb + po.t_rowptr);
+  P.idx = gb.r == 1 ? sel_idx : (const int32_t*)(pb + po.t_idx);
   P.items = (const WorkItem*)(pb + po.items);
   P.bitmap = (const uint32_t*)(pb + po.bitmap);
   P.cu = t.cu; P.qb_off = t.qb_off; P.qb_seq = t.qb_seq; P.bm_off = t.bm_off;

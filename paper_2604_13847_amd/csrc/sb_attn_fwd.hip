@@ -366,13 +366,14 @@ using namespace sb;
 extern "C" int sb_sparse_attn_fwd(const sb_problem* p, const void* q, const void* k, const void* v,
                                   const int32_t* sel_rowptr, const int32_t* sel_idx, const void* plan, void* o,
                                   float* lse, void* ws, void* stream) {
-  Geo g;
-  int rc = make_geo(p, &g);
+  Geo gb;
+  int rc = make_geo(p, &gb);
   if (rc != SB_OK) return rc;
-  if (g.S == 0 || g.T == 0 || g.NQB == 0) return SB_OK;
+  if (gb.S == 0 || gb.T == 0 || gb.NQB == 0) return SB_OK;
+  const Geo g = tile_geo(gb);  // the kernels work on 64-row tiles; for larger selection blocks the plan holds the tile-level selection
   if (!q || !k || !v || !sel_rowptr || !sel_idx || !plan || !o || !lse || !ws) { set_error("null argument"); return SB_ERR_INVALID_ARG; }
   hipStream_t st = (hipStream_t)stream;
-  PlanOffsets po = plan_offsets(g);
+  PlanOffsets po = plan_offsets(gb);
   WsOffsets wo = fwd_ws_offsets(g);
   const char* pb = (const char*)plan;
   char* wb = (char*)ws;
@@ -387,7 +388,8 @@ extern "C" int sb_sparse_attn_fwd(const sb_problem* p, const void* q, const void
     P.q = (const bf16*)q; P.k = (const bf16*)k; P.v = (const bf16*)v;
   }
   P.o = o; P.lse = lse;
-  P.rowptr = sel_rowptr; P.idx = sel_idx; P.work = (const int32_t*)(pb + po.work_fwd);
+  P.rowptr = gb.r == 1 ? sel_rowptr : (const int32_t*)(pb + po.t_rowptr);
+  P.idx = gb.r == 1 ? sel_idx : (const int32_t*)(pb + po.t_idx); P.work = (const int32_t*)(pb + po.work_fwd);
   P.items = (const WorkItem*)(pb + po.items);
   P.cu = t.cu; P.qb_off = t.qb_off; P.qb_seq = t.qb_seq; P.bm_off = t.bm_off;
   P.NQB = g.NQB; P.T = g.T; P.Hq = g.Hq; P.Hkv = g.Hkv; P.G = g.G; P.Hs = g.Hs; P.mode = g.mode;

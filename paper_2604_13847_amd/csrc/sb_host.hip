@@ -47,10 +47,13 @@ int make_geo(const sb_problem* p, Geo* g) {
     set_error("bad select_mode %d", p->select_mode);
     return SB_ERR_INVALID_ARG;
   }
-  if (p->block_size != 64) { set_error("block_size %d unsupported (64 only)", p->block_size); return SB_ERR_UNSUPPORTED; }
+  if (p->block_size != 64 && p->block_size != 128 && p->block_size != 256) {
+    set_error("block_size %d unsupported (64, 128 or 256)", p->block_size);
+    return SB_ERR_UNSUPPORTED;
+  }
   if (p->head_dim != 64 && p->head_dim != 128) { set_error("head_dim %d unsupported (64 or 128)", p->head_dim); return SB_ERR_UNSUPPORTED; }
   g->T = p->total_tokens; g->S = p->num_seqs; g->Hq = p->num_q_heads; g->Hkv = p->num_kv_heads;
-  g->G = g->Hq / g->Hkv; g->D = p->head_dim; g->B = p->block_size; g->mode = p->select_mode; g->dtype = p->dtype;
+  g->G = g->Hq / g->Hkv; g->D = p->head_dim; g->B = p->block_size; g->r = g->B / 64; g->mode = p->select_mode; g->dtype = p->dtype;
   g->Hs = g->mode == SB_SELECT_PER_QHEAD ? g->Hq : g->Hkv;
   if (g->mode == SB_SELECT_PER_KVGROUP && g->G > 8) {
     set_error("SB_SELECT_PER_KVGROUP supports at most 8 query heads per KV head (got %d)", g->G);
@@ -59,6 +62,7 @@ int make_geo(const sb_problem* p, Geo* g) {
   g->softmax_scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)g->D);
   g->score_scale = p->score_scale > 0.f ? p->score_scale : g->softmax_scale;
   g->NQB = 0; g->n_max = 0; g->scores_unit = 0; g->nnz_unit = 0; g->bm_words_unit = 0; g->pairs_unit = 0;
+  g->NT = 0; g->nt_max = 0; g->nnzT_unit = 0; g->bmT_words_unit = 0;
   if (g->S == 0 || g->T == 0) {
     if (g->S > 0 && p->cu_seqlens_host && p->cu_seqlens_host[g->S] != g->T) { set_error("cu_seqlens[S] != T"); return SB_ERR_INVALID_ARG; }
     if (g->S == 0 && g->T != 0) { set_error("T != 0 with S == 0"); return SB_ERR_INVALID_ARG; }
@@ -79,6 +83,11 @@ int make_geo(const sb_problem* p, Geo* g) {
       g->scores_unit += n * n;
       g->nnz_unit += k * n - k * (k - 1) / 2;
       g->bm_words_unit += n * ((n + 31) / 32);
+      const int64_t nt = (L + 63) / 64;
+      g->NT += nt;
+      if (nt > g->nt_max) g->nt_max = (int)nt;
+      g->nnzT_unit += tile_entries_before(nt, k, g->r);
+      g->bmT_words_unit += nt * ((nt + 31) / 32);
       // unmasked pairs: every past selected block is B x B except that the last query block may have
       // fewer rows; the diagonal block contributes rows(rows+1)/2
       for (int64_t i = 0; i < n; ++i) {
@@ -88,7 +97,7 @@ int make_geo(const sb_problem* p, Geo* g) {
       }
     }
   }
-  if ((int64_t)g->Hs * g->nnz_unit > 0x7fffffffLL || (int64_t)g->Hs * g->NQB + 1 > 0x7fffffffLL) {
+  if ((int64_t)g->Hs * g->nnzT_unit > 0x7fffffffLL || (int64_t)g->Hs * g->NT + 1 > 0x7fffffffLL) {
     set_error("selection too large for int32 row pointers");
     return SB_ERR_UNSUPPORTED;
   }
@@ -122,7 +131,8 @@ Tables make_tables(const Geo& g, const sb_problem* p, void* base) {
   return r;
 }
 
-PlanOffsets plan_offsets(const Geo& g) {
+PlanOffsets plan_offsets(const Geo& gb) {
+  const Geo g = tile_geo(gb);  // the plan is laid out for the 64-row tiles the attention kernels work on
   PlanOffsets p{};
   size_t o = 0;
   p.tables = o;   o = align_up(o + table_offsets(g).bytes);
@@ -132,6 +142,13 @@ PlanOffsets plan_offsets(const Geo& g) {
   p.bins = o;     o = align_up(o + sizeof(int32_t) * ((size_t)g.Hkv * kBwdBins + 1));
   p.bitmap = o;   o = align_up(o + sizeof(uint32_t) * (size_t)(g.Hs * g.bm_words_unit + 1));
   p.items = o;    o = align_up(o + sizeof(WorkItem) * (size_t)(g.Hs * g.NQB + 1));
+  p.blk_tables = p.t_rowptr = p.t_idx = p.fbins = o;
+  if (gb.r > 1) {
+    p.fbins = o;      o = align_up(o + sizeof(int32_t) * ((size_t)kBwdBins + 1));
+    p.blk_tables = o; o = align_up(o + table_offsets(gb).bytes);
+    p.t_rowptr = o;   o = align_up(o + sizeof(int32_t) * (size_t)(g.Hs * g.NQB + 1));
+    p.t_idx = o;      o = align_up(o + sizeof(int32_t) * (size_t)(g.Hs * g.nnz_unit + 1));
+  }
   p.bytes = o;
   return p;
 }

@@ -48,7 +48,29 @@ struct Geo {
   int64_t nnz_unit = 0;     // sum_s (k n - k(k-1)/2) (per selection head)
   int64_t bm_words_unit = 0;  // sum_s n_s * ceil(n_s/32) (per selection head)
   int64_t pairs_unit = 0;   // unmasked (query,key) pairs per query head
+  // The attention kernels always work on 64-row tiles.  With a selection block of B = 64*r rows a kept
+  // block stands for r consecutive key tiles and a query block for r query tiles (see plan_expand_kernel).
+  int r = 1;                // tiles per block
+  int64_t NT = 0;           // total 64-row tiles
+  int nt_max = 0;           // largest tile count of a sequence
+  int64_t nnzT_unit = 0;    // tile-level selection entries per selection head
+  int64_t bmT_words_unit = 0;  // sum_s nt_s * ceil(nt_s/32)
 };
+// The same problem as the attention kernels see it: 64-row blocks, tile counts in the block fields.
+inline Geo tile_geo(const Geo& g) {
+  Geo t = g;
+  t.B = 64; t.r = 1; t.NQB = g.NT; t.n_max = g.nt_max; t.nnz_unit = g.nnzT_unit; t.bm_words_unit = g.bmT_words_unit;
+  return t;
+}
+// Tile-level selection entries of the first `it` query tiles of a sequence with budget k (in blocks):
+// query tile it' of block I = it'/r keeps r tiles for each of its min(k, I+1)-1 earlier blocks plus the
+// tiles r*I .. it' of its own block.
+inline __host__ __device__ int64_t tile_entries_before(int64_t it, int64_t k, int64_t r) {
+  const int64_t I = it / r, a = it % r;
+  const int64_t sumc = I <= k ? I * (I - 1) / 2 : k * (k - 1) / 2 + (I - k) * (k - 1);  // sum_{I'<I} (min(k, I'+1) - 1)
+  const int64_t cI = (k < I + 1 ? k : I + 1) - 1;
+  return r * r * sumc + I * (r * (r + 1) / 2) + a * cI * r + a * (a + 1) / 2;
+}
 
 // Validates p and fills g; returns SB_OK or an error (message set).
 int make_geo(const sb_problem* p, Geo* g);
@@ -88,6 +110,11 @@ struct PlanOffsets {
   size_t bins;       // int32 [Hkv*kBwdBins + 1] counting-sort cursors
   size_t bitmap;     // uint32 [Hs * bm_words_unit] transpose bitmap: bit i of column (s,hs,j)
   size_t items;      // WorkItem [Hs*NQB]  descriptors of the query-major items, in work_fwd order
+  // only for selection blocks larger than a tile (r > 1); everything above is then at tile level
+  size_t blk_tables; // TableOffsets area of the block-level geometry
+  size_t t_rowptr;   // int32 [Hs*NT+1]  tile-level selection CSR
+  size_t t_idx;      // int32 [Hs*nnzT]
+  size_t fbins;      // int32 [kBwdBins+1] counting-sort cursors of the query-major items
   size_t bytes;
 };
 constexpr int kBwdBins = 4096;

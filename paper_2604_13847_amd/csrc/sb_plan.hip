@@ -112,19 +112,79 @@ __global__ __launch_bounds__(256) void plan_bwd_scatter_kernel(const int32_t* __
   work_bwd[(int64_t)rank * Hkv + g] = (int32_t)c;
 }
 
+// ---- selection blocks larger than a tile (B = 64 r, r > 1) -------------------------------------
+// The attention kernels work on 64-row tiles.  Query tile it of block I = it / r keeps, for every
+// earlier block J its block kept, the r key tiles rJ .. rJ+r-1 (whole blocks in the past), and of
+// its own block the tiles rI .. it (causality inside the diagonal block, at tile granularity; the
+// token-level mask stays inside tile it).  One wavefront per tile row writes the tile-level CSR.
+__global__ __launch_bounds__(256) void plan_expand_kernel(const int32_t* __restrict__ b_rowptr, const int32_t* __restrict__ b_idx,
+                                                          const int32_t* __restrict__ cu, const int32_t* __restrict__ b_qb_off,
+                                                          const int32_t* __restrict__ kclamp, const int32_t* __restrict__ t_qb_off,
+                                                          const int32_t* __restrict__ t_qb_seq, int S, int64_t NQB, int64_t NT, int Hs,
+                                                          int r, int64_t nnzT_unit, int32_t* __restrict__ t_rowptr,
+                                                          int32_t* __restrict__ t_idx) {
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // hs * NT + global tile
+  if (row >= (int64_t)Hs * NT) return;
+  const int lane = threadIdx.x & 63;
+  const int hs = (int)(row / NT);
+  const int64_t qt = row - (int64_t)hs * NT;
+  const int s = t_qb_seq[qt];
+  const int it = (int)(qt - t_qb_off[s]);
+  int64_t base = 0;  // entries of the earlier sequences (one selection head)
+  for (int t = 0; t < s; ++t) base += tile_entries_before(t_qb_off[t + 1] - t_qb_off[t], kclamp[t], r);
+  const int64_t k = kclamp[s];
+  const int64_t e0 = (int64_t)hs * nnzT_unit + base + tile_entries_before(it, k, r);
+  const int I = it / r, a = it % r;
+  const int64_t brow = (int64_t)hs * NQB + b_qb_off[s] + I;
+  const int be0 = b_rowptr[brow], past = b_rowptr[brow + 1] - be0 - 1;  // kept earlier blocks
+  if (lane == 0) {
+    t_rowptr[row] = (int32_t)e0;
+    if (row == (int64_t)Hs * NT - 1) t_rowptr[row + 1] = (int32_t)(e0 + (int64_t)past * r + a + 1);
+  }
+  for (int x = lane; x < past * r; x += 64) t_idx[e0 + x] = b_idx[be0 + x / r] * r + x % r;
+  for (int x = lane; x <= a; x += 64) t_idx[e0 + (int64_t)past * r + x] = I * r + x;
+}
+
+// Query-major items in order of decreasing cost by a counting sort (the closed-form rank of
+// plan_fwd_kernel only holds for r = 1): histogram, suffix scan, scatter.
+__global__ __launch_bounds__(256) void plan_fwd_hist_kernel(const int32_t* __restrict__ rowptr, int64_t rows, int32_t* __restrict__ bins) {
+  const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (row >= rows) return;
+  atomicAdd(&bins[min(rowptr[row + 1] - rowptr[row], kBwdBins - 1)], 1);
+}
+
+__global__ __launch_bounds__(256) void plan_fwd_scatter_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ qb_off,
+                                                               const int32_t* __restrict__ qb_seq, const int32_t* __restrict__ cu,
+                                                               int64_t rows, int64_t NQB, int32_t* __restrict__ bins,
+                                                               int32_t* __restrict__ work_fwd, WorkItem* __restrict__ items) {
+  const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (row >= rows) return;
+  const int e0 = rowptr[row], c = rowptr[row + 1] - e0;
+  const int pos = atomicAdd(&bins[min(c, kBwdBins - 1)], 1);
+  const int hs = (int)(row / NQB);
+  const int qb = (int)(row - (int64_t)hs * NQB);
+  const int s = qb_seq[qb];
+  work_fwd[pos] = (int32_t)row;
+  WorkItem it;
+  it.row = (int32_t)row; it.seq0 = cu[s]; it.len = cu[s + 1] - cu[s]; it.i = qb - qb_off[s];
+  it.e0 = e0; it.ntiles = c; it.hs = hs; it.s = s;
+  items[pos] = it;
+}
+
 }  // namespace sb
 
 using namespace sb;
 
 extern "C" int sb_plan_worklist(const sb_problem* p, const int32_t* sel_rowptr, const int32_t* sel_idx, void* plan_out,
                                 void* stream) {
-  Geo g;
-  int rc = make_geo(p, &g);
+  Geo gb;
+  int rc = make_geo(p, &gb);
   if (rc != SB_OK) return rc;
-  if (g.S == 0 || g.T == 0 || g.NQB == 0) return SB_OK;
+  if (gb.S == 0 || gb.T == 0 || gb.NQB == 0) return SB_OK;
   if (!sel_rowptr || !sel_idx || !plan_out) { set_error("null sel_rowptr, sel_idx or plan_out"); return SB_ERR_INVALID_ARG; }
   hipStream_t st = (hipStream_t)stream;
-  PlanOffsets po = plan_offsets(g);
+  const Geo g = tile_geo(gb);  // everything below is at the granularity of the 64-row tiles
+  PlanOffsets po = plan_offsets(gb);
   char* base = (char*)plan_out;
   rc = launch_geom(g, p, base + po.tables, st);
   if (rc != SB_OK) return rc;
@@ -136,12 +196,33 @@ extern "C" int sb_plan_worklist(const sb_problem* p, const int32_t* sel_rowptr, 
   uint32_t* bitmap = (uint32_t*)(base + po.bitmap);
   const int64_t rows = (int64_t)g.Hs * g.NQB, ncol = (int64_t)g.Hkv * g.NQB;
   KernelTimer kt(K_PLAN, st);
-  // colcost, work_bwd, bins and bitmap are adjacent: clear colcost, bins and bitmap
+  // colcost, work_bwd, bins, bitmap (and what follows) are adjacent: clear colcost, bins, bitmap and the item cursors
   if ((rc = fill_zero(colcost, po.bytes - po.colcost, st)) != SB_OK) return rc;
-  hipLaunchKernelGGL(plan_fwd_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, t.qb_off, t.kclamp, t.qb_seq,
-                     t.cu, sel_rowptr, g.S, g.NQB, g.Hs, g.Hkv, g.G, g.mode, work_fwd, (WorkItem*)(base + po.items));
-  SB_LAUNCH_CHECK("plan_fwd_kernel");
-  hipLaunchKernelGGL(plan_transpose_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, sel_rowptr, sel_idx, t.qb_off,
+  const int32_t* rowptr = sel_rowptr;
+  const int32_t* idx = sel_idx;
+  if (gb.r == 1) {
+    hipLaunchKernelGGL(plan_fwd_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, t.qb_off, t.kclamp, t.qb_seq,
+                       t.cu, sel_rowptr, g.S, g.NQB, g.Hs, g.Hkv, g.G, g.mode, work_fwd, (WorkItem*)(base + po.items));
+    SB_LAUNCH_CHECK("plan_fwd_kernel");
+  } else {
+    rc = launch_geom(gb, p, base + po.blk_tables, st);
+    if (rc != SB_OK) return rc;
+    Tables tb = make_tables(gb, p, base + po.blk_tables);
+    int32_t* t_rowptr = (int32_t*)(base + po.t_rowptr);
+    int32_t* t_idx = (int32_t*)(base + po.t_idx);
+    int32_t* fbins = (int32_t*)(base + po.fbins);
+    hipLaunchKernelGGL(plan_expand_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, sel_rowptr, sel_idx, t.cu, tb.qb_off,
+                       tb.kclamp, t.qb_off, t.qb_seq, g.S, gb.NQB, g.NQB, g.Hs, gb.r, g.nnz_unit, t_rowptr, t_idx);
+    SB_LAUNCH_CHECK("plan_expand_kernel");
+    rowptr = t_rowptr;
+    idx = t_idx;
+    hipLaunchKernelGGL(plan_fwd_hist_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, rowptr, rows, fbins);
+    hipLaunchKernelGGL(plan_bwd_scan_kernel, dim3(1), dim3(1024), 0, st, fbins);
+    hipLaunchKernelGGL(plan_fwd_scatter_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, rowptr, t.qb_off, t.qb_seq, t.cu,
+                       rows, g.NQB, fbins, work_fwd, (WorkItem*)(base + po.items));
+    SB_LAUNCH_CHECK("plan_fwd counting sort");
+  }
+  hipLaunchKernelGGL(plan_transpose_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, rowptr, idx, t.qb_off,
                      t.bm_off, t.qb_seq, g.NQB, g.Hs, g.G, g.mode, bitmap, colcost);
   SB_LAUNCH_CHECK("plan_transpose_kernel");
   hipLaunchKernelGGL(plan_bwd_hist_kernel, dim3((unsigned)((ncol + 255) / 256)), dim3(256), 0, st, colcost, ncol, g.NQB, bins);

@@ -192,6 +192,13 @@ def config5(seed=0, total=262144, long_len=131072, long_first=True):
     return Workload("cfg5", lens, 32, 8, 128, keep_ratio=ratios.astype(np.float32), seed=seed)
 
 
+def config_block256(seed=0, total=65536):
+    """The block size and budget of the paper's own runs (section 5: MoBA with block 256, top-k 32) on the 60/40
+    length mix of config3, with the head shape of Qwen2.5-3B (16 query heads on 2 KV heads, head_dim 128)."""
+    lens = mixed_lengths(seed, total, short=(1024, 8192), long=(16384, 32768))
+    return Workload("blk256", lens, 16, 2, 128, B=256, topk=[32] * len(lens), seed=seed)
+
+
 def small_ragged(seed=0, lens=(200, 64, 1, 130, 77), Hq=4, Hkv=2, D=64, B=64, ratio=(0.3, 1.0), dtype="bf16"):
     """A small packed batch with ragged tails, several tiles per sequence; for element-wise parity."""
     return Workload("small", list(lens), Hq, Hkv, D, B=B,

@@ -167,3 +167,34 @@ def test_empty_problem_is_a_noop():
     sb.sb_sparse_attn_bwd(pb, z, z, z, o, lse, z, rowptr, idx, plan)
     torch.cuda.synchronize()
     assert rowptr.cpu().numpy()[0] == 0
+
+
+@pytest.mark.parametrize("B", [128, 256])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_selection_blocks_larger_than_a_tile(B, mode):
+    """Selection blocks of 128 / 256 tokens (the block size of the paper's own runs is 256): scores, selection and
+    attention against the checker run with the same block size, element by element."""
+    w = synth.small_ragged(seed=4 + B, lens=(1500, B, 1, 0, B + 1, 2 * B - 1, 2300, 64), Hq=6, Hkv=2, D=128, B=B, ratio=(0.25, 0.8))
+    r = Run(w, mode)
+    q, k, v, do = r.oracle_inputs()
+    ref_sc = orc.block_scores(r.opb, q, k, r.scale)
+    got_sc = r.scores.cpu().numpy()[: r.pb.layout.scores_elems]
+    fin = np.isfinite(ref_sc)
+    assert np.array_equal(np.isneginf(got_sc), np.isneginf(ref_sc))
+    assert np.abs(got_sc[fin] - ref_sc[fin]).max() <= 2e-5 * max(1e-3, np.abs(ref_sc[fin]).max())
+    rp, idx = orc.select_topk(r.opb, got_sc, r.topk)
+    assert np.array_equal(rp, r.rowptr_h) and np.array_equal(idx, r.idx_h)
+    O, LSE = orc.attn_fwd(r.opb, q, k, v, r.rowptr_h, r.idx_h, r.scale)
+    dQ, dK, dV = orc.attn_bwd(r.opb, q, k, v, do, r.rowptr_h, r.idx_h, r.scale)
+    for name, got, ref in (("O", r.o, O), ("dQ", r.dq, dQ), ("dK", r.dk, dK), ("dV", r.dv, dV)):
+        print(name, check_close(name, to_host_f32(got), ref))
+    assert np.abs(r.lse.cpu().numpy() - LSE).max() <= 1e-2
+
+
+def test_block_256_full_budget_is_dense_causal():
+    w = synth.small_ragged(seed=9, lens=(1000, 300), Hq=2, Hkv=1, D=64, B=256, ratio=(1.0, 1.0))
+    r = Run(w, 0)
+    dense = synth.Workload("dense64", w.lens, 2, 1, 64, B=64, keep_ratio=[1.0, 1.0], seed=9)   # same tokens, 64-token blocks, everything kept
+    r64 = Run(dense, 0)
+    for a, b in ((r.o, r64.o), (r.dq, r64.dq), (r.dk, r64.dk), (r.dv, r64.dv)):
+        assert np.abs(to_host_f32(a) - to_host_f32(b)).max() <= 2e-2

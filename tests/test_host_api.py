@@ -25,7 +25,15 @@ def test_library_exports_every_declared_symbol():
     assert "gfx950" in sb.sb_version()
 
 
-@pytest.mark.parametrize("maker", [synth.config1, synth.config2, synth.config3, synth.config5, synth.small_ragged])
+def _ragged_b256(seed):
+    return synth.small_ragged(seed, lens=(3000, 64, 1, 700, 0, 257, 5000), B=256, ratio=(0.2, 0.9))
+
+
+def _ragged_b128(seed):
+    return synth.small_ragged(seed, lens=(3000, 64, 1, 700, 0, 257, 5000), B=128, ratio=(0.2, 0.9))
+
+
+@pytest.mark.parametrize("maker", [synth.config1, synth.config2, synth.config3, synth.config5, synth.small_ragged, _ragged_b128, _ragged_b256])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_layout_matches_checker_counts(maker, mode):
     w = maker(1)
@@ -63,7 +71,7 @@ def _problem(**kw):
 
 
 @pytest.mark.parametrize("kw,code", [
-    (dict(Hq=3), -1), (dict(D=96), -2), (dict(B=128), -2), (dict(topk=[0]), -1), (dict(cu_seqlens=[0, 50, 40]), -1),
+    (dict(Hq=3), -1), (dict(D=96), -2), (dict(B=96), -2), (dict(B=512), -2), (dict(topk=[0]), -1), (dict(cu_seqlens=[0, 50, 40]), -1),
     (dict(cu_seqlens=[1, 100]), -1), (dict(dtype=7), -1), (dict(select_mode=3), -1),
     (dict(Hq=18, Hkv=2, select_mode=1), -2), (dict(cu_seqlens=[0, 64 * 16385], topk=[1]), -2),
 ])
