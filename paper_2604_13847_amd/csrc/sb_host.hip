@@ -142,9 +142,8 @@ PlanOffsets plan_offsets(const Geo& gb) {
   p.bins = o;     o = align_up(o + sizeof(int32_t) * ((size_t)g.Hkv * kBwdBins + 1));
   p.bitmap = o;   o = align_up(o + sizeof(uint32_t) * (size_t)(g.Hs * g.bm_words_unit + 1));
   p.items = o;    o = align_up(o + sizeof(WorkItem) * (size_t)(g.Hs * g.NQB + 1));
-  p.blk_tables = p.t_rowptr = p.t_idx = p.fbins = o;
+  p.blk_tables = p.t_rowptr = p.t_idx = o;
   if (gb.r > 1) {
-    p.fbins = o;      o = align_up(o + sizeof(int32_t) * ((size_t)kBwdBins + 1));
     p.blk_tables = o; o = align_up(o + table_offsets(gb).bytes);
     p.t_rowptr = o;   o = align_up(o + sizeof(int32_t) * (size_t)(g.Hs * g.NQB + 1));
     p.t_idx = o;      o = align_up(o + sizeof(int32_t) * (size_t)(g.Hs * g.nnz_unit + 1));

@@ -114,7 +114,6 @@ struct PlanOffsets {
   size_t blk_tables; // TableOffsets area of the block-level geometry
   size_t t_rowptr;   // int32 [Hs*NT+1]  tile-level selection CSR
   size_t t_idx;      // int32 [Hs*nnzT]
-  size_t fbins;      // int32 [kBwdBins+1] counting-sort cursors of the query-major items
   size_t bytes;
 };
 constexpr int kBwdBins = 4096;

@@ -145,30 +145,33 @@ __global__ __launch_bounds__(256) void plan_expand_kernel(const int32_t* __restr
   for (int x = lane; x <= a; x += 64) t_idx[e0 + (int64_t)past * r + x] = I * r + x;
 }
 
-// Query-major items in order of decreasing cost by a counting sort (the closed-form rank of
-// plan_fwd_kernel only holds for r = 1): histogram, suffix scan, scatter.
-__global__ __launch_bounds__(256) void plan_fwd_hist_kernel(const int32_t* __restrict__ rowptr, int64_t rows, int32_t* __restrict__ bins) {
+// Query-major items for r > 1.  The tile count of a row grows with the query tile until the budget
+// saturates, so "later query tiles first" is close to longest-first, keeps the heads of one query
+// tile adjacent (KV head fastest, see plan_fwd_kernel) and is a closed form again: the position of
+// (s, it, hs) counts the rows of all sequences with a larger tile index, then the rows with the same
+// tile index in earlier sequences.
+__global__ __launch_bounds__(256) void plan_fwd_tiles_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ qb_off,
+                                                             const int32_t* __restrict__ qb_seq, const int32_t* __restrict__ cu, int S,
+                                                             int64_t NQB, int Hs, int Hkv, int G, int mode,
+                                                             int32_t* __restrict__ work_fwd, WorkItem* __restrict__ items) {
   const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (row >= rows) return;
-  atomicAdd(&bins[min(rowptr[row + 1] - rowptr[row], kBwdBins - 1)], 1);
-}
-
-__global__ __launch_bounds__(256) void plan_fwd_scatter_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ qb_off,
-                                                               const int32_t* __restrict__ qb_seq, const int32_t* __restrict__ cu,
-                                                               int64_t rows, int64_t NQB, int32_t* __restrict__ bins,
-                                                               int32_t* __restrict__ work_fwd, WorkItem* __restrict__ items) {
-  const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (row >= rows) return;
-  const int e0 = rowptr[row], c = rowptr[row + 1] - e0;
-  const int pos = atomicAdd(&bins[min(c, kBwdBins - 1)], 1);
+  if (row >= (int64_t)Hs * NQB) return;
   const int hs = (int)(row / NQB);
   const int qb = (int)(row - (int64_t)hs * NQB);
   const int s = qb_seq[qb];
+  const int it = qb - qb_off[s];
+  int64_t pos = 0;
+  for (int t = 0; t < S; ++t) {
+    const int nt = qb_off[t + 1] - qb_off[t];
+    if (nt > it + 1) pos += (int64_t)Hs * (nt - 1 - it);  // rows of t with a larger tile index
+    if (t < s && nt > it) pos += Hs;                      // same tile index, earlier sequence
+  }
+  pos += mode == SB_SELECT_PER_QHEAD ? (hs % G) * Hkv + hs / G : hs;
   work_fwd[pos] = (int32_t)row;
-  WorkItem it;
-  it.row = (int32_t)row; it.seq0 = cu[s]; it.len = cu[s + 1] - cu[s]; it.i = qb - qb_off[s];
-  it.e0 = e0; it.ntiles = c; it.hs = hs; it.s = s;
-  items[pos] = it;
+  WorkItem w;
+  w.row = (int32_t)row; w.seq0 = cu[s]; w.len = cu[s + 1] - cu[s]; w.i = it;
+  w.e0 = rowptr[row]; w.ntiles = rowptr[row + 1] - w.e0; w.hs = hs; w.s = s;
+  items[pos] = w;
 }
 
 }  // namespace sb
@@ -210,17 +213,14 @@ extern "C" int sb_plan_worklist(const sb_problem* p, const int32_t* sel_rowptr, 
     Tables tb = make_tables(gb, p, base + po.blk_tables);
     int32_t* t_rowptr = (int32_t*)(base + po.t_rowptr);
     int32_t* t_idx = (int32_t*)(base + po.t_idx);
-    int32_t* fbins = (int32_t*)(base + po.fbins);
     hipLaunchKernelGGL(plan_expand_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, sel_rowptr, sel_idx, t.cu, tb.qb_off,
                        tb.kclamp, t.qb_off, t.qb_seq, g.S, gb.NQB, g.NQB, g.Hs, gb.r, g.nnz_unit, t_rowptr, t_idx);
     SB_LAUNCH_CHECK("plan_expand_kernel");
     rowptr = t_rowptr;
     idx = t_idx;
-    hipLaunchKernelGGL(plan_fwd_hist_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, rowptr, rows, fbins);
-    hipLaunchKernelGGL(plan_bwd_scan_kernel, dim3(1), dim3(1024), 0, st, fbins);
-    hipLaunchKernelGGL(plan_fwd_scatter_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, rowptr, t.qb_off, t.qb_seq, t.cu,
-                       rows, g.NQB, fbins, work_fwd, (WorkItem*)(base + po.items));
-    SB_LAUNCH_CHECK("plan_fwd counting sort");
+    hipLaunchKernelGGL(plan_fwd_tiles_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, rowptr, t.qb_off, t.qb_seq, t.cu, g.S,
+                       g.NQB, g.Hs, g.Hkv, g.G, g.mode, work_fwd, (WorkItem*)(base + po.items));
+    SB_LAUNCH_CHECK("plan_fwd_tiles_kernel");
   }
   hipLaunchKernelGGL(plan_transpose_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, rowptr, idx, t.qb_off,
                      t.bm_off, t.qb_seq, g.NQB, g.Hs, g.G, g.mode, bitmap, colcost);
