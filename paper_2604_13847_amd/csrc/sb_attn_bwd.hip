@@ -86,7 +86,7 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
     for (int a = tid; a < kJ; a += nthr) jbuf[a] = t0 + a < ntiles ? P.idx[e0 + t0 + a] : 0;
     __syncthreads();
   };
-  TileLoader<D> loader;
+  TileLoader<D, 4> loader;  // every workgroup of this kernel has at least four wavefronts: they share the tile loads
   loader.init(P.Hkv, wave, lane);
   auto issue = [&](int t) {
     const int j = __builtin_amdgcn_readfirstlane(jbuf[t % kJ]);

@@ -153,11 +153,12 @@ __device__ inline void wait_vmcnt() {
 // Per-lane byte offsets (from the tile's first row, head h) of the D/16 loads a loader wavefront
 // issues for a tile: load a covers tile rows (wave + 2a)*RPI .. +RPI-1.  They depend only on the
 // lane and on the tensor's row pitch, so they are computed once per kernel.
-template <int D>
+template <int D, int NW = 2>  // NW: wavefronts (0 .. NW-1 of the workgroup) that share the loads of a tile
 struct TileLoader {
   static constexpr int C = D / 8;      // 16-byte chunks per row
   static constexpr int RPI = 64 / C;   // rows covered by one wavefront-wide load
-  static constexpr int LPT = D / 16;   // loads per loader wavefront per tile
+  static constexpr int LPT = (D / 8) / NW;  // loads per loader wavefront per tile
+  static_assert(LPT >= 1 && LPT * NW * RPI == 64, "the loader wavefronts must cover the 64 rows exactly");
   unsigned voff[LPT];
   int rl, pc;  // row within a load's group of RPI rows, 16-byte chunk of this lane
   int wave;
@@ -167,16 +168,16 @@ struct TileLoader {
     pc = lane % C;
 #pragma unroll
     for (int a = 0; a < LPT; ++a) {
-      const int r = ((wave & 1) + 2 * a) * RPI + rl;
+      const int r = ((wave & (NW - 1)) + NW * a) * RPI + rl;
       voff[a] = (unsigned)(r * H * D * 2 + 16 * (pc ^ chunk_swizzle<D>(r)));
     }
   }
   // Issue the copy of rows row0 .. row0+63 (head h) of `src` into `slot`.  Rows >= valid repeat the
-  // last valid row; their data is always masked by the consumer.  Wavefronts 0 and 1 issue LPT loads
+  // last valid row; their data is always masked by the consumer.  Wavefronts 0 .. NW-1 issue LPT loads
   // each, the others none.  Full tiles (the common case) use a scalar base address plus the
   // precomputed lane offsets, so no vector arithmetic is spent per load.
   __device__ inline void issue(bf16* slot, const bf16* src, int64_t row0, int valid, int H, int h) const {
-    if (wave >= 2) return;
+    if (wave >= NW) return;
     const unsigned base = lds_offset(slot);
     const char* tile = (const char*)(src + (row0 * H + h) * D);
     if (valid >= 64) {
@@ -188,12 +189,12 @@ struct TileLoader {
 #pragma unroll
       for (int a = 0; a < LPT; ++a)
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %0, %1"
-                     : : "v"(voff[a]), "s"(ts), "s"(base + ((wave & 1) + 2 * a) * 1024) : "memory", "m0");
+                     : : "v"(voff[a]), "s"(ts), "s"(base + ((wave & (NW - 1)) + NW * a) * 1024) : "memory", "m0");
     } else {
 #pragma unroll
       for (int a = 0; a < LPT; ++a) {  // ragged tile (rare): the lane offsets are recomputed instead of being kept in registers
-        const int r = ((wave & 1) + 2 * a) * RPI + rl;
-        dma16(tile + (int64_t)min(r, valid - 1) * H * D * 2 + 16 * (pc ^ chunk_swizzle<D>(r)), base + ((wave & 1) + 2 * a) * 1024);
+        const int r = ((wave & (NW - 1)) + NW * a) * RPI + rl;
+        dma16(tile + (int64_t)min(r, valid - 1) * H * D * 2 + 16 * (pc ^ chunk_swizzle<D>(r)), base + ((wave & (NW - 1)) + NW * a) * 1024);
       }
     }
   }
