@@ -206,6 +206,14 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
       for (int q = 0; q < 2; ++q)
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt) dqacc[dt] = mfma32(op[q * (D / 32) + dt], dsb[q], dqacc[dt]);
+      // the matrix instructions of the first 16 keys run under the pointwise work of the other 16
+      __builtin_amdgcn_sched_group_barrier(0x002, 40, 0);
+#pragma unroll
+      for (int i_ = 0; i_ < D / 32; ++i_) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 40 / (D / 32), 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, D / 32, 0);
     }
   }
   if (KS == 2) {  // add the two key halves of every row: the kh = 1 wavefront hands its partial over
