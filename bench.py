@@ -76,7 +76,8 @@ def main():
     ap.add_argument("--mode", default="per_qhead", choices=["per_qhead", "per_kvgroup"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cu-busy", action="store_true", help="also report the per-CU busy-time spread")
+    ap.add_argument("--cu-busy", action="store_true", help="(default) also report the per-CU busy-time spread")
+    ap.add_argument("--no-cu-busy", action="store_true", help="skip the two instrumented launches that measure the per-CU busy-time spread")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every box has one); use --gpus 1", file=sys.stderr)
@@ -170,7 +171,7 @@ def main():
                      "flops_per_launch": dom_flops, "avg_launch_ms": round(kavg[dom], 4)},
     }
 
-    if args.cu_busy:
+    if not args.no_cu_busy:  # outside the timed region: one instrumented forward and one instrumented backward
         spreads = {}
         for name, call in (("fwd", lambda: L.sb_sparse_attn_fwd(pb.ref(), P(q), P(k), P(v), P(rowptr), P(idx), P(plan), P(o), P(lse), P(ws_fwd), st)),
                            ("bwd", lambda: L.sb_sparse_attn_bwd(pb.ref(), P(q), P(k), P(v), P(o), P(lse), P(do), P(rowptr), P(idx), P(plan), P(dq), P(dk), P(dv), P(ws_bwd), st))):
