@@ -27,7 +27,7 @@ MEASURED_TRAFFIC_BYTES = {("cfg2", "per_qhead"): {"fwd": 1.004e9 + 0.273e9, "bwd
 def make_workload(name, seed):
     from paper_2604_13847_amd import synth
     return {"cfg1": synth.config1, "cfg2": synth.config2, "cfg3": synth.config3, "cfg4": synth.config4,
-            "cfg5": synth.config5, "blk256": synth.config_block256}[name](seed)
+            "cfg5": synth.config5, "blk256": synth.config_block256, "d64": synth.config_d64}[name](seed)
 
 
 def cpu_baseline(w, host, opb, topk, rowptr_h, idx_h, scale, budget_s=15.0):

@@ -199,6 +199,13 @@ def config_block256(seed=0, total=65536):
     return Workload("blk256", lens, 16, 2, 128, B=256, topk=[32] * len(lens), seed=seed)
 
 
+def config_d64(seed=0, total=65536):
+    """As config_block256 with the head shape of Qwen2.5-0.5B, the smaller model of the paper's runs (section 5):
+    14 query heads on 2 KV heads, head_dim 64."""
+    lens = mixed_lengths(seed, total, short=(1024, 8192), long=(16384, 32768))
+    return Workload("d64", lens, 14, 2, 64, B=256, topk=[32] * len(lens), seed=seed)
+
+
 def small_ragged(seed=0, lens=(200, 64, 1, 130, 77), Hq=4, Hkv=2, D=64, B=64, ratio=(0.3, 1.0), dtype="bf16"):
     """A small packed batch with ragged tails, several tiles per sequence; for element-wise parity."""
     return Workload("small", list(lens), Hq, Hkv, D, B=B,

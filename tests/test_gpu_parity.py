@@ -215,3 +215,13 @@ def test_sixteen_query_heads_on_one_kv_head_per_qhead():
         mx, mn = err_stats(to_host_f32(got), ref)
         print(name, mx, mn)
         assert mx <= 2 * MAX_ABS and mn <= MEAN_ABS
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_head_dim_64_seven_heads_per_kv_head_block_256(mode):
+    """The head shape of the smaller model of the paper's runs (section 5: 14 query heads on 2 KV heads, head_dim 64)
+    with the block size of those runs."""
+    w = synth.small_ragged(seed=21, lens=(1100, 257, 700), Hq=14, Hkv=2, D=64, B=256, ratio=(0.3, 0.8))
+    r = Run(w, mode)
+    check_selection(r, check_scores(r))
+    print(w, "mode", mode, check_attention(r), flush=True)
