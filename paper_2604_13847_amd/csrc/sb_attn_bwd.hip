@@ -1,6 +1,6 @@
 // Block-sparse attention backward (gradient of paper Eq. 2 with the selection held fixed).
 //
-//   Dr = rowsum(dO * O)                                    (prep kernel)
+//   Dr = rowsum(dO * O)                                    (prologue of the query-major kernel, which owns every row once)
 //   P  = exp(scale * S - LSE),  dP = dO V^T,  dS = P * (dP - Dr)
 //   dQ = scale * dS K          query-major kernel, same work items and tile walk as the forward
 //   dK = scale * dS^T Q, dV = P^T dO   key-major kernel: one workgroup owns key block (s, g, j),
@@ -14,44 +14,14 @@
 namespace sb {
 
 // ---------------------------------------------------------------------------------------------
-// Dr = rowsum(dO * O) and the log-sum-exp in base 2 (LSE * log2 e), both [Hq][T]
-template <bool O_F32>
-__global__ __launch_bounds__(256) void bwd_prep_kernel(const void* __restrict__ o, const bf16* __restrict__ d_o, int64_t rows,
-                                                       int T, int Hq, int D, const float* __restrict__ lse,
-                                                       float* __restrict__ drow, float* __restrict__ lse2) {
-  const int lpr = D / 8;  // lanes per (token, head) row, 8 elements each
-  const int64_t r = ((int64_t)blockIdx.x * 256 + threadIdx.x) / lpr;
-  const int c = threadIdx.x % lpr;
-  float acc = 0.f;
-  if (r < rows) {
-    bf16x8 a = *(const bf16x8*)(d_o + r * D + 8 * c);
-    if (O_F32) {
-      const float* op = (const float*)o + r * D + 8 * c;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc += (float)a[e] * op[e];
-    } else {
-      bf16x8 b = *(const bf16x8*)((const bf16*)o + r * D + 8 * c);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc += (float)a[e] * (float)b[e];
-    }
-  }
-  for (int off = lpr >> 1; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
-  if (r < rows && c == 0) {
-    const int64_t t = r / Hq;
-    const int h = (int)(r - t * Hq);
-    drow[(int64_t)h * T + t] = acc;
-    lse2[(int64_t)h * T + t] = lse[(int64_t)h * T + t] * 1.4426950408889634f;
-  }
-  if (blockIdx.x == 0 && threadIdx.x == 0) lse2[(int64_t)Hq * T] = __builtin_inff();  // read in place of the LSE of rows that do not exist
-}
-
-// ---------------------------------------------------------------------------------------------
 // Query-major dQ kernel.  Same work items as the forward.  A workgroup takes one item (sequence,
 // selection head, query block) and HPW query heads that share its selection (one in per-query-head
 // mode); the K and V tiles of the selected blocks are double-buffered in LDS as whole tiles by
 // asynchronous loads and shared by all wavefronts of the workgroup.  A wavefront owns 32 query rows
 // of one head and, with the key split KS = 2, one 32-key half of every tile (the two partial dQ of a
-// row are added through LDS at the end); Q, dO, LSE and Dr of its rows stay in registers.
+// row are added through LDS at the end); Q, dO, LSE and Dr of its rows stay in registers.  Every (token,
+// query head) row belongs to exactly one workgroup of this kernel, so its prologue is also where Dr is
+// computed (from the dO registers and one read of O) and left, with LSE * log2 e, for the key-major kernel.
 // Transposed products put a query in a C-matrix column: S^T = K Q^T, dP^T = V dO^T, so LSE and Dr are
 // per-lane scalars and dS^T converts to the B operand of dQ^T += K^T dS^T without cross-lane movement;
 // K^T comes from the row-major K tile through the transposing LDS read.
@@ -107,10 +77,34 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
       qf[ks] = qvalid ? *(const bf16x8*)(qp + 16 * ks) : zero_bf16x8();
       dof[ks] = qvalid ? *(const bf16x8*)(dp + 16 * ks) : zero_bf16x8();
     }
+    // Dr of the lane's query: its half of the head dimension here, the other half in lane ^ 32
+    float part = 0.f;
     if (qvalid) {
-      lse2 = P.lse2[(int64_t)h * P.T + tq];
-      dr = P.drow[(int64_t)h * P.T + tq];
+      if (OUT_F32) {
+        const float* op_ = (const float*)P.o + (tq * P.Hq + h) * D + 8 * hf;
+#pragma unroll
+        for (int ks = 0; ks < NOP; ++ks) {
+          const float4 a = *(const float4*)(op_ + 16 * ks), b = *(const float4*)(op_ + 16 * ks + 4);
+          part += (float)dof[ks][0] * a.x + (float)dof[ks][1] * a.y + (float)dof[ks][2] * a.z + (float)dof[ks][3] * a.w;
+          part += (float)dof[ks][4] * b.x + (float)dof[ks][5] * b.y + (float)dof[ks][6] * b.z + (float)dof[ks][7] * b.w;
+        }
+      } else {
+        const bf16* op_ = (const bf16*)P.o + (tq * P.Hq + h) * D + 8 * hf;
+#pragma unroll
+        for (int ks = 0; ks < NOP; ++ks) {
+          const bf16x8 ov = *(const bf16x8*)(op_ + 16 * ks);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) part += (float)dof[ks][e] * (float)ov[e];
+        }
+      }
+      lse2 = P.lse[(int64_t)h * P.T + tq] * 1.4426950408889634f;
     }
+    dr = part + __shfl_xor(part, 32, 64);
+    if (qvalid && kh == 0 && hf == 0) {
+      P.drow[(int64_t)h * P.T + tq] = dr;
+      P.lse2[(int64_t)h * P.T + tq] = lse2;
+    }
+    if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) P.lse2[(int64_t)P.Hq * P.T] = __builtin_inff();  // read by the key-major kernel in place of the LSE of rows that do not exist
   }
   stage_indices(0);
   // everything loaded so far must have landed before the tile loads start (see the forward kernel)
@@ -662,6 +656,7 @@ extern "C" int sb_sparse_attn_bwd(const sb_problem* p, const void* q, const void
   AttnParams P{};
   const bool f32 = g.dtype == SB_F32;
   if (f32) {
+    KernelTimer kt(K_BWD_PREP, st);  // float32 inputs only: the conversions to the kernels' operand type
     if ((rc = convert_f32_to_bf16(q, wb + wo.qc, (int64_t)g.T * g.Hq * g.D, st)) != SB_OK) return rc;
     if ((rc = convert_f32_to_bf16(k, wb + wo.kc, (int64_t)g.T * g.Hkv * g.D, st)) != SB_OK) return rc;
     if ((rc = convert_f32_to_bf16(v, wb + wo.vc, (int64_t)g.T * g.Hkv * g.D, st)) != SB_OK) return rc;
@@ -673,7 +668,7 @@ extern "C" int sb_sparse_attn_bwd(const sb_problem* p, const void* q, const void
   }
   float* drow = (float*)(wb + wo.drow);
   float* lse2 = (float*)(wb + wo.lse2);
-  P.lse = (float*)lse; P.drow = drow; P.lse2 = lse2; P.dq = dq; P.dk = dk; P.dv = dv;
+  P.o = (void*)o; P.lse = (float*)lse; P.drow = drow; P.lse2 = lse2; P.dq = dq; P.dk = dk; P.dv = dv;
   P.rowptr = gb.r == 1 ? sel_rowptr : (const int32_t*)(pb + po.t_rowptr);
   P.idx = gb.r == 1 ? sel_idx : (const int32_t*)(pb + po.t_idx);
   P.items = (const WorkItem*)(pb + po.items);
@@ -687,16 +682,6 @@ extern "C" int sb_sparse_attn_bwd(const sb_problem* p, const void* q, const void
     if ((rc = fill_zero(wb + wo.cu_busy, sizeof(uint64_t) * SB_CU_SLOTS, st)) != SB_OK) return rc;
     P.cu_busy = (unsigned long long*)(wb + wo.cu_busy);
   }
-  const int64_t rows = (int64_t)g.T * g.Hq;
-  const int rows_per_wg = 256 / (g.D / 8);
-  dim3 pgrid((unsigned)((rows + rows_per_wg - 1) / rows_per_wg));
-  {
-  KernelTimer kt(K_BWD_PREP, st);
-  if (f32) hipLaunchKernelGGL(bwd_prep_kernel<true>, pgrid, dim3(256), 0, st, o, P.d_o, rows, g.T, g.Hq, g.D, lse, drow, lse2);
-  else hipLaunchKernelGGL(bwd_prep_kernel<false>, pgrid, dim3(256), 0, st, o, P.d_o, rows, g.T, g.Hq, g.D, lse, drow, lse2);
-  }
-  SB_LAUNCH_CHECK("bwd_prep_kernel");
-
   AttnParams Pq = P, Pk = P;
   Pq.work = (const int32_t*)(pb + po.work_fwd);
   Pk.work = (const int32_t*)(pb + po.work_bwd);

@@ -16,8 +16,8 @@ struct AttnParams {
   const bf16* q; const bf16* k; const bf16* v; const bf16* d_o;
   void* o;            // forward output (bf16 or float per out_f32)
   float* lse;         // [Hq][T]
-  const float* drow;  // [Hq][T] rowsum(dO * O)
-  const float* lse2;  // [Hq][T] lse * log2(e)
+  float* drow;        // [Hq][T] rowsum(dO * O): written by the dQ kernel, read by the dK/dV kernel
+  float* lse2;        // [Hq][T] lse * log2(e), likewise; entry [Hq*T] is +inf (stands in for rows that do not exist)
   void* dq; void* dk; void* dv;
   const int32_t* rowptr; const int32_t* idx; const int32_t* work;
   const WorkItem* items;  // descriptors of the query-major items, in work order
