@@ -342,6 +342,196 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
   timer.stop(P);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Forward kernel for per-KV-group selection: the query heads of a KV group share a work item, so one
+// workgroup takes 3 or 4 of them and they share the item's K/V tiles in LDS (whole tiles,
+// double-buffered by asynchronous loads) instead of fetching them once per head.  Two wavefronts per
+// query head; a wavefront owns 32 query rows and all 64 keys of every selected tile, as two 32-key
+// halves with one online-softmax step each.  The register budget (256) lets two wavefronts share a
+// SIMD, so one runs its exponentials while the other runs matrix instructions; one operand set
+// rotates through both contractions (K rows, then V^T through the transposing read, each register
+// refilled right after the MFMA that consumed it).
+template <int D, bool OUT_F32>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void attn_fwd_group_kernel(AttnParams P, int heads) {
+  constexpr int TILE_B = 64 * D * 2, ROW_B = D * 2, NOP = D / 16;
+  constexpr float kLazy = 8.0f;
+  __shared__ __attribute__((aligned(1024))) bf16 tiles[2][2][64 * D];  // [buffer][K, V]
+  constexpr int kJ = 256;
+  __shared__ int jbuf[kJ];
+  BusyTimer timer;
+  timer.start(P);
+  const int tid = threadIdx.x, nthr = blockDim.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+  const WorkItem item = P.items[blockIdx.x];
+  const int hs = item.hs, i = item.i, L = item.len, e0 = item.e0, ntiles = item.ntiles;
+  const int64_t seq0 = item.seq0;
+  const int strip = wave & 1;
+  const int hh = blockIdx.y * (nthr / 128) + (wave >> 1);  // query head of the group this wavefront works for
+  const bool head_ok = hh < heads;
+  const int h = hs * P.G + (head_ok ? hh : 0);  // per-KV-group mode: the item's selection head is the KV head
+  const int g = hs;
+  const int qloc = strip * 32 + l32;
+  const bool qvalid = head_ok && i * 64 + qloc < L;
+  const int64_t tq = seq0 + i * 64 + qloc;
+
+  auto stage_indices = [&](int t0) {
+    __syncthreads();
+    for (int a = tid; a < kJ; a += nthr) jbuf[a] = t0 + a < ntiles ? P.idx[e0 + t0 + a] : 0;
+    __syncthreads();
+  };
+  TileLoader<D, 4> loader;  // a workgroup has six or eight wavefronts: the first four share the tile loads
+  loader.init(P.Hkv, wave, lane);
+  auto issue = [&](int t) {
+    const int j = __builtin_amdgcn_readfirstlane(jbuf[t % kJ]);
+    const int64_t kv0 = seq0 + (int64_t)j * 64;
+    const int kvalid = min(64, L - j * 64);
+    loader.issue(tiles[t & 1][0], P.k, kv0, kvalid, P.Hkv, g);
+    loader.issue(tiles[t & 1][1], P.v, kv0, kvalid, P.Hkv, g);
+  };
+
+  // B operand of S^T = K Q^T: column = query lane%32 of the strip, slots = d 16ks + 8hf + (0..7)
+  bf16x8 qf[NOP];
+  {
+    const bf16* qp = P.q + (tq * P.Hq + h) * D + 8 * hf;
+#pragma unroll
+    for (int ks = 0; ks < NOP; ++ks) qf[ks] = qvalid ? *(const bf16x8*)(qp + 16 * ks) : zero_bf16x8();
+  }
+  stage_indices(0);
+  // everything loaded so far must have landed before the tile loads start: from here on the only
+  // vector-memory operations in flight are tile loads, which the loop waits for by count
+#pragma unroll
+  for (int ks = 0; ks < NOP; ++ks) asm volatile("" : "+v"(qf[ks]));
+  issue(0);
+
+  const unsigned tiles0 = lds_offset(&tiles[0][0][0]);
+  unsigned row_a[NOP], tr_a[D / 32][2];
+#pragma unroll
+  for (int ks = 0; ks < NOP; ++ks) row_a[ks] = tiles0 + l32 * ROW_B + 16 * ((2 * ks + hf) ^ chunk_swizzle<D>(l32));
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int r = 8 * half + 4 * hf + ((lane & 15) >> 2), d = 32 * dt + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+      tr_a[dt][half] = tiles0 + TILE_B + r * ROW_B + 16 * ((d >> 3) ^ chunk_swizzle<D>(r)) + 2 * (d & 7);
+    }
+  auto ld_row = [&](int ks, unsigned off) __attribute__((always_inline)) {
+    return *(const bf16x8 __attribute__((address_space(3)))*)(row_a[ks] + off);
+  };
+  // A operand of O^T += V^T P^T: row = d (32dt + lane%32), slots = keys 16kk + 8(e/4) + 4hf + e%4 of this wavefront's rows
+  auto ld_tr = [&](int kk, int dt) __attribute__((always_inline)) {
+    const unsigned o = kk * 16 * ROW_B;
+    bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(tr_a[dt][0] + o));
+    bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(tr_a[dt][1] + o));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  };
+
+  f32x16 oacc[D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt) oacc[dt] = zero16();
+  float m = -__builtin_inff(), l = 0.f;
+  bf16x8 op[NOP];
+
+  for (int t = 0; t < ntiles; ++t) {
+    const bool more = t + 1 < ntiles;
+    if (more && (t + 1) % kJ == 0) stage_indices(t + 1);
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();  // tile t has landed for everyone; everyone is done with tile t-1
+    if (more) issue(t + 1);
+    if (t > 0) {  // the operand addresses follow the tile into the other buffer
+      const int dl = (t & 1) ? 2 * TILE_B : -2 * TILE_B;
+#pragma unroll
+      for (int ks = 0; ks < NOP; ++ks) row_a[ks] += dl;
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt) { tr_a[dt][0] += dl; tr_a[dt][1] += dl; }
+    }
+    const bool diag = t == ntiles - 1;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {  // keys 32mt .. 32mt+31 of the tile
+#pragma unroll
+      for (int ks = 0; ks < NOP; ++ks) op[ks] = ld_row(ks, mt * 32 * ROW_B);  // K rows
+      __builtin_amdgcn_sched_barrier(0);
+      f32x16 sacc = zero16();
+#pragma unroll
+      for (int ks = 0; ks < NOP; ++ks) {  // S^T = K Q^T, refilling every operand register with a V^T operand
+        sacc = mfma32(op[ks], qf[ks], sacc);
+        op[ks] = ld_tr(2 * mt + ks / (D / 32), ks % (D / 32));
+      }
+#pragma unroll
+      for (int i_ = 0; i_ < NOP; ++i_) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (diag) {  // causal mask inside the diagonal block (also removes keys past the end of the sequence)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (32 * mt + c_row(v, hf) > qloc) sacc[v] = -__builtin_inff();
+      }
+      // online softmax with a lazy running maximum: the reference m follows the true maximum only when
+      // that has grown by more than kLazy (in log2 units), so p stays below 2^kLazy and the accumulated
+      // O is rescaled only then; O and the row sum carry the same factor, so the result is the same
+      float mx = max3(sacc[0], sacc[1], sacc[2]);
+#pragma unroll
+      for (int v = 3; v < 15; v += 2) mx = max3(mx, sacc[v], sacc[v + 1]);
+      mx = max_across_halves(fmaxf(mx, sacc[15]));
+      const bool first = m == -__builtin_inff();  // nothing accumulated yet for this query
+      const bool move = first | ((mx - m) * P.scale_log2e > kLazy);
+      const float m_new = move ? fmaxf(m, mx) : m;
+      const float m_use = m_new == -__builtin_inff() ? 0.f : m_new;  // no unmasked key seen yet: keep the exponent finite
+      const float alpha = first ? 1.0f : fast_exp2((m - m_use) * P.scale_log2e);
+      const float neg_m = -m_use * P.scale_log2e;
+      bf16x8 pb[2];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) pb[v >> 3][v & 7] = (bf16)fast_exp2(__builtin_fmaf(sacc[v], P.scale_log2e, neg_m));
+      float rs = l * alpha;  // the row sum adds the probabilities as rounded to bf16, the weights the accumulation applies
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        const bf16x8 x = pb[kk];
+        rs = sum2(__builtin_shufflevector(x, x, 0, 1), rs);
+        rs = sum2(__builtin_shufflevector(x, x, 2, 3), rs);
+        rs = sum2(__builtin_shufflevector(x, x, 4, 5), rs);
+        rs = sum2(__builtin_shufflevector(x, x, 6, 7), rs);
+      }
+      l = rs;
+      m = m_new;
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+      }
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt) oacc[dt] = mfma32(op[kk * (D / 32) + dt], pb[kk], oacc[dt]);
+    }
+  }
+
+  l += __shfl_xor(l, 32, 64);  // the two lane halves hold different keys of the same query
+  if (qvalid) {
+    const float inv = 1.0f / l;  // l > 0 for every existing query: its own key is never masked
+    const int64_t obase = (tq * P.Hq + h) * D;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int vg = 0; vg < 4; ++vg) {
+        const int d0 = 32 * dt + 8 * vg + 4 * hf;
+        float x[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = oacc[dt][4 * vg + e] * inv;
+        if (OUT_F32) {
+          *(float4*)((float*)P.o + obase + d0) = make_float4(x[0], x[1], x[2], x[3]);
+        } else {
+          bf16x4 y;
+          y[0] = (bf16)x[0]; y[1] = (bf16)x[1]; y[2] = (bf16)x[2]; y[3] = (bf16)x[3];
+          *(bf16x4*)((bf16*)P.o + obase + d0) = y;
+        }
+      }
+    if (hf == 0) P.lse[(int64_t)h * P.T + tq] = (m * P.scale_log2e + __builtin_log2f(l)) * 0.69314718055994531f;
+  }
+  timer.stop(P);
+}
+
 // float -> bf16 (round to nearest even) copy used when the caller's tensors are float
 __global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float* __restrict__ src, bf16* __restrict__ dst, int64_t n4) {
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -402,17 +592,30 @@ extern "C" int sb_sparse_attn_fwd(const sb_problem* p, const void* q, const void
   }
   const int heads = g.mode == SB_SELECT_PER_QHEAD ? 1 : g.G;  // query heads that share a work item
   const int64_t n_items = (int64_t)g.Hs * g.NQB;
-  const int64_t n_wg = (n_items + 7) / 8 * 8 * heads;
-  if (n_wg > 0x7fffffffll) { set_error("too many work items for one launch"); return SB_ERR_INVALID_ARG; }
-  dim3 grid((unsigned)n_wg), block(128);
+  const int parts = (heads + 3) / 4, hpp = (heads + parts - 1) / parts;  // the group kernel takes `hpp` heads per workgroup
   KernelTimer kt(K_FWD, st);
-#define SB_FWD_LAUNCH(DD, FF) hipLaunchKernelGGL((attn_fwd_kernel<DD, FF>), grid, block, 0, st, P, (int)n_items, heads)
-  if (g.D == 128) {
-    if (P.out_f32) SB_FWD_LAUNCH(128, true); else SB_FWD_LAUNCH(128, false);
-  } else {
-    if (P.out_f32) SB_FWD_LAUNCH(64, true); else SB_FWD_LAUNCH(64, false);
-  }
+  if (hpp >= 3 && parts * hpp == heads) {  // heads share K/V tiles in LDS; with a head slot left idle the per-head kernel is faster
+    if (n_items > 0x7fffffffll) { set_error("too many work items for one launch"); return SB_ERR_INVALID_ARG; }
+    dim3 grid((unsigned)n_items, (unsigned)parts), block(128 * hpp);
+#define SB_FWD_LAUNCH(DD, FF) hipLaunchKernelGGL((attn_fwd_group_kernel<DD, FF>), grid, block, 0, st, P, heads)
+    if (g.D == 128) {
+      if (P.out_f32) SB_FWD_LAUNCH(128, true); else SB_FWD_LAUNCH(128, false);
+    } else {
+      if (P.out_f32) SB_FWD_LAUNCH(64, true); else SB_FWD_LAUNCH(64, false);
+    }
 #undef SB_FWD_LAUNCH
+  } else {
+    const int64_t n_wg = (n_items + 7) / 8 * 8 * heads;
+    if (n_wg > 0x7fffffffll) { set_error("too many work items for one launch"); return SB_ERR_INVALID_ARG; }
+    dim3 grid((unsigned)n_wg), block(128);
+#define SB_FWD_LAUNCH(DD, FF) hipLaunchKernelGGL((attn_fwd_kernel<DD, FF>), grid, block, 0, st, P, (int)n_items, heads)
+    if (g.D == 128) {
+      if (P.out_f32) SB_FWD_LAUNCH(128, true); else SB_FWD_LAUNCH(128, false);
+    } else {
+      if (P.out_f32) SB_FWD_LAUNCH(64, true); else SB_FWD_LAUNCH(64, false);
+    }
+#undef SB_FWD_LAUNCH
+  }
   SB_LAUNCH_CHECK("attn_fwd_kernel");
   return SB_OK;
 }

@@ -225,3 +225,12 @@ def test_head_dim_64_seven_heads_per_kv_head_block_256(mode):
     r = Run(w, mode)
     check_selection(r, check_scores(r))
     print(w, "mode", mode, check_attention(r), flush=True)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("D", [64, 128])
+def test_four_heads_per_kv_group_share_tiles(D, dtype):
+    """Per-KV-group selection with four query heads per KV head: the forward kernel that shares the K/V tiles of an item
+    between the group's heads (ragged tails, a 1-token and an empty sequence, more than one tile per row)."""
+    w = synth.small_ragged(seed=17, lens=(330, 64, 1, 0, 129, 500), Hq=8, Hkv=2, D=D, ratio=(0.3, 0.9), dtype=dtype)
+    full_check(w, sb.SB_SELECT_PER_KVGROUP)
