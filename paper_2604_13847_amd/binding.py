@@ -308,8 +308,7 @@ def plan_views(pb: Problem, plan: torch.Tensor):
     tables_bytes = o
     o = up(tables_bytes)
     off = {}
-    for name, size in (("work_fwd", 4 * (Hs * NQB + 1)), ("colcost", 4 * (Hkv * NQB + 1)), ("work_bwd", 4 * (Hkv * NQB + 1)),
-                       ("bins", 4 * (Hkv * 4096 + 1))):
+    for name, size in (("work_fwd", 4 * (Hs * NQB + 1)), ("colcost", 4 * (Hkv * NQB + 1)), ("work_bwd", 4 * (Hkv * NQB + 1))):
         off[name] = o
         o = up(o + size)
     off["bitmap"] = o

@@ -139,7 +139,6 @@ PlanOffsets plan_offsets(const Geo& gb) {
   p.work_fwd = o; o = align_up(o + sizeof(int32_t) * (size_t)(g.Hs * g.NQB + 1));
   p.colcost = o;  o = align_up(o + sizeof(int32_t) * (size_t)(g.Hkv * g.NQB + 1));
   p.work_bwd = o; o = align_up(o + sizeof(int32_t) * (size_t)(g.Hkv * g.NQB + 1));
-  p.bins = o;     o = align_up(o + sizeof(int32_t) * ((size_t)g.Hkv * kBwdBins + 1));
   p.bitmap = o;   o = align_up(o + sizeof(uint32_t) * (size_t)(g.Hs * g.bm_words_unit + 1));
   p.items = o;    o = align_up(o + sizeof(WorkItem) * (size_t)(g.Hs * g.NQB + 1));
   p.blk_tables = p.t_rowptr = p.t_idx = o;

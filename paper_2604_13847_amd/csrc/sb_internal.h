@@ -107,7 +107,6 @@ struct PlanOffsets {
   size_t work_fwd;   // int32 [Hs*NQB]   row ids, longest first
   size_t colcost;    // int32 [Hkv*NQB]  tiles in each key-major column (summed over the group's heads)
   size_t work_bwd;   // int32 [Hkv*NQB]  column ids (g*NQB + qb): entry r*Hkv + g is the r-th heaviest column of KV head g
-  size_t bins;       // int32 [Hkv*kBwdBins + 1] counting-sort cursors
   size_t bitmap;     // uint32 [Hs * bm_words_unit] transpose bitmap: bit i of column (s,hs,j)
   size_t items;      // WorkItem [Hs*NQB]  descriptors of the query-major items, in work_fwd order
   // only for selection blocks larger than a tile (r > 1); everything above is then at tile level

@@ -8,9 +8,9 @@
 // ranks differ in the KV head first, so with workgroups dealt round-robin to the 8 XCDs each XCD's
 // L2 keeps seeing the same KV heads.
 //
-// Key-major transpose.  Bit i of word (s,hs,j,i/32) says query block i kept key block j.  Bits are
-// set with atomicOr, whose result does not depend on order, so the backward pass can walk a
-// column's query blocks in ascending order and accumulate deterministically.
+// Key-major transpose.  Bit i of word (s,hs,j,i/32) says query block i kept key block j; the bitmap
+// is a pure function of the selection, so the backward pass walks a column's query blocks in a
+// fixed order and accumulates deterministically.
 #include "sb_internal.h"
 
 namespace sb {
@@ -45,27 +45,55 @@ __global__ __launch_bounds__(256) void plan_fwd_kernel(const int32_t* __restrict
   items[pos] = it;
 }
 
-// one wavefront per CSR row: set the row's bit in each selected column and count the column weights
+// One workgroup per (selection head, sequence, 32 consecutive query blocks) builds word i/32 of
+// every column of the sequence in LDS (LDS atomics) and then stores it: every bitmap word has one
+// owner, so the bitmap needs neither clearing nor global atomics; the column weights get one global
+// add per non-empty word instead of one per selected tile.
+constexpr int kTrChunk = 8192;  // columns handled per pass (32 KiB of LDS)
 __global__ __launch_bounds__(256) void plan_transpose_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ idx,
                                                              const int32_t* __restrict__ qb_off, const int64_t* __restrict__ bm_off,
-                                                             const int32_t* __restrict__ qb_seq, int64_t NQB, int Hs, int G,
-                                                             int mode, uint32_t* __restrict__ bitmap, int32_t* __restrict__ colcost) {
-  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= (int64_t)Hs * NQB) return;
-  const int lane = threadIdx.x & 63;
-  const int hs = (int)(row / NQB);
-  const int qb = (int)(row - (int64_t)hs * NQB);
-  const int s = qb_seq[qb];
-  const int i = qb - qb_off[s];
+                                                             int S, int64_t NQB, int Hs, int G, int mode,
+                                                             uint32_t* __restrict__ bitmap, int32_t* __restrict__ colcost) {
+  __shared__ uint32_t wcol[kTrChunk];
+  __shared__ int sh_s, sh_w;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  if (tid == 0) {
+    int x = blockIdx.x, s = 0;
+    for (; s < S; ++s) {
+      const int w = (qb_off[s + 1] - qb_off[s] + 31) >> 5;
+      if (x < w) break;
+      x -= w;
+    }
+    sh_s = s; sh_w = x;
+  }
+  __syncthreads();
+  const int s = sh_s, wi = sh_w;
+  if (s >= S) return;
+  const int hs = blockIdx.y;
   const int n = qb_off[s + 1] - qb_off[s];
   const int w = (n + 31) >> 5;
   uint32_t* bm = bitmap + (int64_t)Hs * bm_off[s] + (int64_t)hs * n * w;
   const int g = mode == SB_SELECT_PER_QHEAD ? hs / G : hs;
-  const int weight = mode == SB_SELECT_PER_QHEAD ? 1 : G;  // query-head tiles this entry stands for
-  for (int e = rowptr[row] + lane; e < rowptr[row + 1]; e += 64) {
-    const int j = idx[e];
-    atomicOr(&bm[(int64_t)j * w + (i >> 5)], 1u << (i & 31));
-    atomicAdd(&colcost[(int64_t)g * NQB + qb_off[s] + j], weight);
+  const int weight = mode == SB_SELECT_PER_QHEAD ? 1 : G;  // query-head tiles an entry stands for
+  int32_t* cost = colcost + (int64_t)g * NQB + qb_off[s];
+  const int64_t row0 = (int64_t)hs * NQB + qb_off[s] + 32 * wi;
+  const int nrows = min(32, n - 32 * wi);
+  for (int j0 = 0; j0 < n; j0 += kTrChunk) {
+    const int nj = min(kTrChunk, n - j0);
+    for (int j = tid; j < nj; j += 256) wcol[j] = 0u;
+    __syncthreads();
+    for (int r = wave; r < nrows; r += 4)
+      for (int e = rowptr[row0 + r] + lane; e < rowptr[row0 + r + 1]; e += 64) {
+        const int j = idx[e] - j0;
+        if (j >= 0 && j < nj) atomicOr(&wcol[j], 1u << r);
+      }
+    __syncthreads();
+    for (int j = tid; j < nj; j += 256) {
+      const uint32_t x = wcol[j];
+      bm[(int64_t)(j0 + j) * w + wi] = x;
+      if (x) atomicAdd(&cost[j0 + j], weight * __popc(x));
+    }
+    __syncthreads();
   }
 }
 
@@ -73,27 +101,28 @@ __global__ __launch_bounds__(256) void plan_transpose_kernel(const int32_t* __re
 // are interleaved (position = rank_in_g * Hkv + g).  Neighbouring workgroups of one KV head then
 // walk neighbouring key blocks of one sequence and meet the same Q/dO tiles in the L2 of their XCD
 // at about the same time, while the heaviest-first rule still holds inside each list.
-__global__ __launch_bounds__(256) void plan_bwd_hist_kernel(const int32_t* __restrict__ colcost, int64_t ncol, int64_t NQB,
-                                                            int32_t* __restrict__ bins) {
-  const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (c >= ncol) return;
-  atomicAdd(&bins[(c / NQB) * kBwdBins + min(colcost[c], kBwdBins - 1)], 1);
-}
-
-// one workgroup per KV head: bins[b] <- number of its columns with cost bin > b
-__global__ __launch_bounds__(1024) void plan_bwd_scan_kernel(int32_t* __restrict__ bins_all) {
+// One workgroup per KV head: a counting sort on the column weight in LDS (histogram, suffix sums,
+// scatter); columns of equal weight end up in no particular order.
+__global__ __launch_bounds__(1024) void plan_bwd_order_kernel(const int32_t* __restrict__ colcost, int64_t NQB, int Hkv,
+                                                              int32_t* __restrict__ work_bwd) {
+  __shared__ int bins[kBwdBins];
   __shared__ int sh[1024];
-  int32_t* bins = bins_all + (int64_t)blockIdx.x * kBwdBins;
   const int tid = threadIdx.x;
+  const int64_t g = blockIdx.x;
+  const int32_t* cost = colcost + g * NQB;
+  for (int b = tid; b < kBwdBins; b += 1024) bins[b] = 0;
+  __syncthreads();
+  for (int64_t c = tid; c < NQB; c += 1024) atomicAdd(&bins[min(cost[c], kBwdBins - 1)], 1);
+  __syncthreads();
+  // bins[b] <- number of columns with a bin > b; thread t owns bins (kBwdBins-1 - t*per) downwards
   constexpr int per = kBwdBins / 1024;
   int v[per], sum = 0;
-  // thread t owns bins (kBwdBins-1 - t*per) downwards
 #pragma unroll
   for (int a = 0; a < per; ++a) { v[a] = bins[kBwdBins - 1 - (tid * per + a)]; sum += v[a]; }
   sh[tid] = sum;
   __syncthreads();
   for (int off = 1; off < 1024; off <<= 1) {
-    int t = tid >= off ? sh[tid - off] : 0;
+    const int t = tid >= off ? sh[tid - off] : 0;
     __syncthreads();
     sh[tid] += t;
     __syncthreads();
@@ -101,15 +130,11 @@ __global__ __launch_bounds__(1024) void plan_bwd_scan_kernel(int32_t* __restrict
   int run = sh[tid] - sum;
 #pragma unroll
   for (int a = 0; a < per; ++a) { bins[kBwdBins - 1 - (tid * per + a)] = run; run += v[a]; }
-}
-
-__global__ __launch_bounds__(256) void plan_bwd_scatter_kernel(const int32_t* __restrict__ colcost, int64_t ncol, int64_t NQB, int Hkv,
-                                                               int32_t* __restrict__ bins, int32_t* __restrict__ work_bwd) {
-  const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (c >= ncol) return;
-  const int64_t g = c / NQB;
-  const int rank = atomicAdd(&bins[g * kBwdBins + min(colcost[c], kBwdBins - 1)], 1);
-  work_bwd[(int64_t)rank * Hkv + g] = (int32_t)c;
+  __syncthreads();
+  for (int64_t c = tid; c < NQB; c += 1024) {
+    const int rank = atomicAdd(&bins[min(cost[c], kBwdBins - 1)], 1);
+    work_bwd[(int64_t)rank * Hkv + g] = (int32_t)(g * NQB + c);
+  }
 }
 
 // ---- selection blocks larger than a tile (B = 64 r, r > 1) -------------------------------------
@@ -195,12 +220,10 @@ extern "C" int sb_plan_worklist(const sb_problem* p, const int32_t* sel_rowptr, 
   int32_t* work_fwd = (int32_t*)(base + po.work_fwd);
   int32_t* colcost = (int32_t*)(base + po.colcost);
   int32_t* work_bwd = (int32_t*)(base + po.work_bwd);
-  int32_t* bins = (int32_t*)(base + po.bins);
   uint32_t* bitmap = (uint32_t*)(base + po.bitmap);
   const int64_t rows = (int64_t)g.Hs * g.NQB, ncol = (int64_t)g.Hkv * g.NQB;
   KernelTimer kt(K_PLAN, st);
-  // colcost, work_bwd, bins, bitmap (and what follows) are adjacent: clear colcost, bins, bitmap and the item cursors
-  if ((rc = fill_zero(colcost, po.bytes - po.colcost, st)) != SB_OK) return rc;
+  if ((rc = fill_zero(colcost, sizeof(int32_t) * (size_t)ncol, st)) != SB_OK) return rc;  // the only part of the plan that is accumulated into
   const int32_t* rowptr = sel_rowptr;
   const int32_t* idx = sel_idx;
   if (gb.r == 1) {
@@ -222,13 +245,15 @@ extern "C" int sb_plan_worklist(const sb_problem* p, const int32_t* sel_rowptr, 
                        g.NQB, g.Hs, g.Hkv, g.G, g.mode, work_fwd, (WorkItem*)(base + po.items));
     SB_LAUNCH_CHECK("plan_fwd_tiles_kernel");
   }
-  hipLaunchKernelGGL(plan_transpose_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, rowptr, idx, t.qb_off,
-                     t.bm_off, t.qb_seq, g.NQB, g.Hs, g.G, g.mode, bitmap, colcost);
+  int64_t words = 0;  // (sequence, 32 query blocks) pairs
+  for (int s = 0; s < g.S; ++s) {
+    const int64_t L = (int64_t)p->cu_seqlens_host[s + 1] - p->cu_seqlens_host[s];
+    words += ((L + g.B - 1) / g.B + 31) / 32;
+  }
+  hipLaunchKernelGGL(plan_transpose_kernel, dim3((unsigned)words, (unsigned)g.Hs), dim3(256), 0, st, rowptr, idx, t.qb_off, t.bm_off,
+                     g.S, g.NQB, g.Hs, g.G, g.mode, bitmap, colcost);
   SB_LAUNCH_CHECK("plan_transpose_kernel");
-  hipLaunchKernelGGL(plan_bwd_hist_kernel, dim3((unsigned)((ncol + 255) / 256)), dim3(256), 0, st, colcost, ncol, g.NQB, bins);
-  hipLaunchKernelGGL(plan_bwd_scan_kernel, dim3((unsigned)g.Hkv), dim3(1024), 0, st, bins);
-  hipLaunchKernelGGL(plan_bwd_scatter_kernel, dim3((unsigned)((ncol + 255) / 256)), dim3(256), 0, st, colcost, ncol, g.NQB,
-                     g.Hkv, bins, work_bwd);
+  hipLaunchKernelGGL(plan_bwd_order_kernel, dim3((unsigned)g.Hkv), dim3(1024), 0, st, colcost, g.NQB, g.Hkv, work_bwd);
   SB_LAUNCH_CHECK("plan_bwd kernels");
   return SB_OK;
 }
