@@ -1,6 +1,7 @@
 // Routing scores (paper section 2.2, MoBA indexer): mean-pool the blocks of K and Q, then
 // score = score_scale * <pooled Q block i, pooled K block j> for past blocks j < i.
-// Both kernels are HBM-bound: K and Q are read once, the score matrix is written once.
+// Pooling is HBM-bound (K and Q are read once); the score tiles run on the fp32 matrix cores and
+// write the score matrix once.
 #include "sb_internal.h"
 
 namespace sb {
@@ -42,31 +43,51 @@ __global__ __launch_bounds__(256) void pool_kernel(const void* __restrict__ X, i
   *(float4*)(out + (int64_t)qb * cols + c0) = make_float4(a0 * inv, a1 * inv, a2 * inv, a3 * inv);
 }
 
-// One workgroup per (tile of 64 query blocks of one sequence, selection head).  It walks the key
-// block tiles (32 key blocks each) up to its own diagonal, computing 64x32 scores per step from
-// LDS-staged pooled vectors, and writes -infinity for every j >= i of its rows.
-// tile table: grid.x indexes (sequence, i-tile) pairs through a search over it_off (prefix of ceil(n_s/64)).
+// Score tiles on the fp32 matrix cores (v_mfma_f32_32x32x2_f32: the selection is taken on fp32
+// scores, so the operands stay fp32).  One workgroup per (64 query blocks of one sequence, chunk of
+// up to kScChunk * 64 key blocks, selection head): the pooled query tile is staged in LDS once, the
+// pooled key tiles one after the other; each of the four wavefronts computes a 32 x 32 quarter of
+// every 64 x 64 score tile.  Tiles right of the diagonal are -infinity without being computed, and
+// the last chunk of a row tile also fills every column to its right with -infinity, so that the
+// whole n x n matrix is defined.  Splitting the columns over workgroups keeps the longest workgroup
+// short however long the sequence is.
+constexpr int kScChunk = 4;
+typedef float f32x16s __attribute__((ext_vector_type(16)));
+
+// workgroups of a sequence with nt row tiles: sum over it < nt of (it / kScChunk + 1)
+__host__ __device__ inline int64_t score_items(int64_t nt) {
+  const int64_t q = nt / kScChunk, r = nt % kScChunk;
+  return kScChunk * q * (q + 1) / 2 + r * (q + 1);
+}
+
 template <int D>
 __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ qbar, const float* __restrict__ kbar,
-                                                    const int32_t* __restrict__ cu, const int32_t* __restrict__ qb_off,
-                                                    const int64_t* __restrict__ sc_off, int S, int Hq, int Hkv, int Hs,
-                                                    int G, int mode, float scale, float* __restrict__ scores) {
+                                                    const int32_t* __restrict__ qb_off, const int64_t* __restrict__ sc_off,
+                                                    int S, int Hq, int Hkv, int Hs, int G, int mode, float scale,
+                                                    float* __restrict__ scores) {
   constexpr int LD = D + 4;  // padded row length (floats) of the LDS tiles
   __shared__ float qs[64 * LD];
-  __shared__ float ks[32 * LD];
-  __shared__ int sh_s, sh_it;
+  __shared__ float ks[64 * LD];
+  __shared__ int sh_s, sh_it, sh_jc;
   const int tid = threadIdx.x;
-  if (tid == 0) {  // locate (sequence, i-tile) of this workgroup
-    int t = blockIdx.x, s = 0;
+  if (tid == 0) {  // locate (sequence, row tile, column chunk) of this workgroup
+    int64_t x = blockIdx.x;
+    int s = 0, it = 0;
     for (; s < S; ++s) {
-      int nt = (qb_off[s + 1] - qb_off[s] + 63) >> 6;
-      if (t < nt) break;
-      t -= nt;
+      const int64_t c = score_items((qb_off[s + 1] - qb_off[s] + 63) >> 6);
+      if (x < c) break;
+      x -= c;
     }
-    sh_s = s; sh_it = t;
+    if (s < S)
+      for (;; ++it) {
+        const int c = it / kScChunk + 1;
+        if (x < c) break;
+        x -= c;
+      }
+    sh_s = s; sh_it = it; sh_jc = (int)x;
   }
   __syncthreads();
-  const int s = sh_s, it = sh_it;
+  const int s = sh_s, it = sh_it, jc = sh_jc;
   if (s >= S) return;
   const int hs = blockIdx.y;
   const int n = qb_off[s + 1] - qb_off[s];
@@ -79,66 +100,67 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ qb
   const int g = h0 / G;
   // stage the pooled query tile (summed over the group's heads in per-KV-group mode)
   for (int u = tid; u < 64 * (D / 4); u += 256) {
-    int r = u / (D / 4), c = (u % (D / 4)) * 4;
+    const int r = u / (D / 4), c = (u % (D / 4)) * 4;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     if (r < rows)
       for (int hh = 0; hh < heads; ++hh) {
-        float4 v = *(const float4*)(qbar + ((qb0 + i0 + r) * Hq + h0 + hh) * D + c);
+        const float4 v = *(const float4*)(qbar + ((qb0 + i0 + r) * Hq + h0 + hh) * D + c);
         acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
       }
     *(float4*)(qs + r * LD + c) = acc;
   }
-  const int ti = tid >> 4, tj = tid & 15;  // thread computes rows ti*4..+3, columns tj and tj+16
+  const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+  const int wr = wave & 1, wc = wave >> 1;  // quarter of the 64 x 64 tile this wavefront computes
   const float ninf = -__builtin_inff();
-  for (int jt = 0; jt <= 2 * it + 1; ++jt) {
-    const int j0 = jt * 32;
+  for (int c = 0; c < kScChunk; ++c) {
+    const int jt = jc * kScChunk + c, j0 = jt * 64;
     if (j0 >= n) break;
-    const int colsv = min(32, n - j0);
-    __syncthreads();
-    for (int u = tid; u < 32 * (D / 4); u += 256) {
-      int r = u / (D / 4), c = (u % (D / 4)) * 4;
+    if (jt > it) {  // entirely in the future of these rows
+      for (int u = tid; u < rows * 64; u += 256) {
+        const int r = u >> 6, j = j0 + (u & 63);
+        if (j < n) out[(int64_t)(i0 + r) * n + j] = ninf;
+      }
+      continue;
+    }
+    __syncthreads();  // the previous key tile has been consumed (and, the first time, the query tile is staged)
+    const int colsv = min(64, n - j0);
+    for (int u = tid; u < 64 * (D / 4); u += 256) {
+      const int r = u / (D / 4), cc = (u % (D / 4)) * 4;
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (r < colsv) v = *(const float4*)(kbar + ((qb0 + j0 + r) * Hkv + g) * D + c);
-      *(float4*)(ks + r * LD + c) = v;
+      if (r < colsv) v = *(const float4*)(kbar + ((qb0 + j0 + r) * Hkv + g) * D + cc);
+      *(float4*)(ks + r * LD + cc) = v;
     }
     __syncthreads();
-    float acc[4][2];
+    // A = pooled queries (row = lane % 32), B = pooled keys transposed (column = lane % 32); the lane half
+    // picks which of the two contraction slots of an instruction it feeds: slot (step 4t + e, half) is d = 8t + 4 half + e
+    f32x16s acc;
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-      for (int b = 0; b < 2; ++b) acc[a][b] = 0.f;
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    const float* qa = qs + (32 * wr + l32) * LD + 4 * hf;
+    const float* kb = ks + (32 * wc + l32) * LD + 4 * hf;
 #pragma unroll 4
-    for (int d = 0; d < D; d += 4) {
-      float4 qv[4], kv[2];
-#pragma unroll
-      for (int a = 0; a < 4; ++a) qv[a] = *(const float4*)(qs + (ti * 4 + a) * LD + d);
-#pragma unroll
-      for (int b = 0; b < 2; ++b) kv[b] = *(const float4*)(ks + (tj + 16 * b) * LD + d);
-#pragma unroll
-      for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-          acc[a][b] = fmaf(qv[a].x, kv[b].x, acc[a][b]);
-          acc[a][b] = fmaf(qv[a].y, kv[b].y, acc[a][b]);
-          acc[a][b] = fmaf(qv[a].z, kv[b].z, acc[a][b]);
-          acc[a][b] = fmaf(qv[a].w, kv[b].w, acc[a][b]);
-        }
+    for (int t = 0; t < D / 8; ++t) {
+      const float4 a = *(const float4*)(qa + 8 * t), b = *(const float4*)(kb + 8 * t);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
     }
+    // C layout: column = lane % 32, register v = row 8 (v / 4) + 4 half + v % 4
+    const int j = j0 + 32 * wc + l32;
+    if (j < n) {
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-      int i = i0 + ti * 4 + a;
-      if (i >= n) continue;
-#pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        int j = j0 + tj + 16 * b;
-        if (j < n) out[(int64_t)i * n + j] = j < i ? scale * acc[a][b] : ninf;
+      for (int v = 0; v < 16; ++v) {
+        const int i = i0 + 32 * wr + 8 * (v >> 2) + 4 * hf + (v & 3);
+        if (i < n) out[(int64_t)i * n + j] = j < i ? scale * acc[v] : ninf;
       }
     }
   }
-  // columns right of the own tile are all in the future
-  const int jstart = (it + 1) * 64;
-  for (int r = 0; r < rows; ++r)
-    for (int j = jstart + tid; j < n; j += 256) out[(int64_t)(i0 + r) * n + j] = ninf;
+  if (jc == it / kScChunk) {  // last chunk of this row tile: every column to its right is in the future
+    const int jstart = (jc + 1) * kScChunk * 64;
+    for (int r = 0; r < rows; ++r)
+      for (int j = jstart + tid; j < n; j += 256) out[(int64_t)(i0 + r) * n + j] = ninf;
+  }
 }
 
 }  // namespace sb
@@ -174,21 +196,21 @@ extern "C" int sb_block_scores(const sb_problem* p, const void* q, const void* k
   SB_LAUNCH_CHECK("pool_kernel");
   if (kbar_out)
     SB_CHECK_HIP(hipMemcpyAsync(kbar_out, kbar, sizeof(float) * (size_t)g.NQB * g.Hkv * g.D, hipMemcpyDeviceToDevice, st));
-  // number of (sequence, i-tile) pairs
-  int64_t tiles = 0;
+  int64_t items = 0;  // (sequence, row tile, column chunk) triples
   for (int s = 0; s < g.S; ++s) {
-    int64_t L = (int64_t)p->cu_seqlens_host[s + 1] - p->cu_seqlens_host[s];
-    int64_t n = (L + g.B - 1) / g.B;
-    tiles += (n + 63) / 64;
+    const int64_t L = (int64_t)p->cu_seqlens_host[s + 1] - p->cu_seqlens_host[s];
+    const int64_t n = (L + g.B - 1) / g.B;
+    items += score_items((n + 63) / 64);
   }
-  dim3 gs((unsigned)tiles, (unsigned)g.Hs);
+  if (items > 0x7fffffffll) { set_error("too many score tiles for one launch"); return SB_ERR_INVALID_ARG; }
+  dim3 gs((unsigned)items, (unsigned)g.Hs);
   KernelTimer kt(K_SCORE, st);
   if (g.D == 128)
-    hipLaunchKernelGGL(score_kernel<128>, gs, dim3(256), 0, st, qbar, kbar, t.cu, t.qb_off, t.sc_off, g.S, g.Hq, g.Hkv,
-                       g.Hs, g.G, g.mode, g.score_scale, scores_out);
+    hipLaunchKernelGGL(score_kernel<128>, gs, dim3(256), 0, st, qbar, kbar, t.qb_off, t.sc_off, g.S, g.Hq, g.Hkv, g.Hs, g.G,
+                       g.mode, g.score_scale, scores_out);
   else
-    hipLaunchKernelGGL(score_kernel<64>, gs, dim3(256), 0, st, qbar, kbar, t.cu, t.qb_off, t.sc_off, g.S, g.Hq, g.Hkv,
-                       g.Hs, g.G, g.mode, g.score_scale, scores_out);
+    hipLaunchKernelGGL(score_kernel<64>, gs, dim3(256), 0, st, qbar, kbar, t.qb_off, t.sc_off, g.S, g.Hq, g.Hkv, g.Hs, g.G,
+                       g.mode, g.score_scale, scores_out);
   SB_LAUNCH_CHECK("score_kernel");
   return SB_OK;
 }
