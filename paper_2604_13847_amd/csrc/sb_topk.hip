@@ -1,7 +1,7 @@
 // Top-K block selection (paper section 2.2): per row (sequence, selection head, query block i)
 // keep the diagonal block plus the best c-1 past blocks under the total order
 // (score descending, block index ascending; -0 == +0; NaN below everything).
-// One workgroup per row: order-preserving 32-bit keys in LDS, a 4-pass radix select for the
+// One wavefront per row: order-preserving 32-bit keys in LDS, a 4-pass radix select for the
 // threshold key, then an index-ordered compaction, so the result is a pure function of the scores.
 #include "sb_internal.h"
 
@@ -14,35 +14,25 @@ __device__ inline uint32_t order_key(float x) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-// exclusive prefix sum over the 256 threads of a workgroup; `tmp` holds 8 ints; returns the total in *total
-__device__ inline int block_excl_scan_256(int v, int* tmp, int* total) {
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  int incl = v;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    int t = __shfl_up(incl, off, 64);
-    if (lane >= off) incl += t;
-  }
-  __syncthreads();  // tmp may still be read from a previous call
-  if (lane == 63) tmp[w] = incl;
-  __syncthreads();
-  int base = 0;
-  for (int a = 0; a < w; ++a) base += tmp[a];
-  *total = tmp[0] + tmp[1] + tmp[2] + tmp[3];
-  return base + incl - v;
-}
+// LDS operations of one wavefront are carried out in issue order, so a wavefront that works alone
+// on its own LDS region needs no barrier between phases: only the compiler has to keep the order.
+__device__ inline void wave_lds_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
+// One wavefront per row (several rows per workgroup, no workgroup barrier anywhere): keys and a
+// 256-bin histogram in the wavefront's own LDS region.
 __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ scores, const int32_t* __restrict__ qb_off,
                                                    const int64_t* __restrict__ sc_off, const int32_t* __restrict__ row_base,
                                                    const int32_t* __restrict__ kclamp, const int32_t* __restrict__ qb_seq,
-                                                   int64_t NQB, int Hs, int64_t nnz_unit, int32_t* __restrict__ rowptr,
-                                                   int32_t* __restrict__ idx) {
-  extern __shared__ uint32_t keys[];  // n_max entries
-  __shared__ int hist[256];
-  __shared__ int tmp[8];
-  __shared__ int sh_bin, sh_above;
-  const int tid = threadIdx.x;
-  const int qb = blockIdx.x, hs = blockIdx.y;
+                                                   int64_t NQB, int Hs, int64_t nnz_unit, int region_words,
+                                                   int32_t* __restrict__ rowptr, int32_t* __restrict__ idx) {
+  extern __shared__ uint32_t smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t row_id = (int64_t)blockIdx.x * (blockDim.x >> 6) + wave;  // hs * NQB + query block
+  if (row_id >= (int64_t)Hs * NQB) return;
+  uint32_t* keys = smem + (size_t)wave * region_words;
+  int* hist = (int*)(keys + region_words - 256);
+  const int hs = (int)(row_id / NQB);
+  const int qb = (int)(row_id - (int64_t)hs * NQB);
   const int s = qb_seq[qb];
   const int i = qb - qb_off[s];
   const int n = qb_off[s + 1] - qb_off[s];
@@ -52,70 +42,84 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ sco
   const int m0 = min(i, k);  // rows i' < i with i'+1 <= k contribute i'+1, the rest contribute k
   const int64_t before = (int64_t)m0 * (m0 + 1) / 2 + (int64_t)(i - m0) * k;
   const int64_t start = (int64_t)hs * nnz_unit + row_base[s] + before;
-  if (tid == 0) {
-    rowptr[(int64_t)hs * NQB + qb] = (int32_t)start;
-    if (hs == Hs - 1 && qb == NQB - 1) rowptr[(int64_t)Hs * NQB] = (int32_t)(start + c);
+  if (lane == 0) {
+    rowptr[row_id] = (int32_t)start;
+    if (row_id == (int64_t)Hs * NQB - 1) rowptr[(int64_t)Hs * NQB] = (int32_t)(start + c);
   }
   int32_t* out = idx + start;
   const int need = c - 1, m = i;  // choose `need` of the m past blocks
   if (need == m) {                // everything is kept (also covers need == 0 with i == 0)
-    for (int j = tid; j <= i; j += 256) out[j] = j;
+    for (int j = lane; j <= i; j += 64) out[j] = j;
     return;
   }
   if (need == 0) {
-    if (tid == 0) out[0] = i;
+    if (lane == 0) out[0] = i;
     return;
   }
   const float* row = scores + (int64_t)Hs * sc_off[s] + ((int64_t)hs * n + i) * n;
-  for (int j = tid; j < m; j += 256) keys[j] = order_key(row[j]);
-  // radix select: the need-th largest key
+  for (int j0 = lane; j0 < m; j0 += 64 * 8) {  // eight independent loads in flight per lane: the row comes from HBM
+    float x[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) x[u] = j0 + 64 * u < m ? row[j0 + 64 * u] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (j0 + 64 * u < m) keys[j0 + 64 * u] = order_key(x[u]);
+  }
+  // radix select, 8 bits per pass: the need-th largest key
   uint32_t prefix = 0, mask = 0;
   int remaining = need;
   for (int shift = 24; shift >= 0; shift -= 8) {
-    hist[tid] = 0;
-    __syncthreads();
-    for (int j = tid; j < m; j += 256) {
-      uint32_t kk = keys[j];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) hist[lane + 64 * a] = 0;
+    wave_lds_fence();
+    for (int j = lane; j < m; j += 64) {
+      const uint32_t kk = keys[j];
       if ((kk & mask) == prefix) atomicAdd(&hist[(kk >> shift) & 255u], 1);
     }
-    __syncthreads();
-    // thread t looks at bin 255-t: `above` = number of matching keys in higher bins
-    int mine = hist[255 - tid], total;
-    int above = block_excl_scan_256(mine, tmp, &total);
-    if (above < remaining && remaining <= above + mine) { sh_bin = 255 - tid; sh_above = above; }
-    __syncthreads();
-    prefix |= (uint32_t)sh_bin << shift;
+    wave_lds_fence();
+    // lane L owns bins 255-4L .. 252-4L (descending); `above` = matching keys in higher bins
+    int v[4], sum = 0;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) { v[a] = hist[255 - 4 * lane - a]; sum += v[a]; }
+    int incl = sum;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int t = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += t;
+    }
+    int run = incl - sum, bin = -1, above = 0;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      if (run < remaining && remaining <= run + v[a]) { bin = 255 - 4 * lane - a; above = run; }
+      run += v[a];
+    }
+    const unsigned long long found = __builtin_amdgcn_ballot_w64(bin >= 0);  // exactly one lane
+    const int src = __builtin_ctzll(found);
+    bin = __shfl(bin, src, 64);
+    above = __shfl(above, src, 64);
+    prefix |= (uint32_t)bin << shift;
     mask |= 255u << shift;
-    remaining -= sh_above;
-    __syncthreads();
+    remaining -= above;
+    wave_lds_fence();  // the histogram is cleared again at the top
   }
-  // keys > prefix are all kept; of the keys == prefix the `remaining` lowest indices are kept
+  // keys > prefix are all kept; of the keys == prefix the `remaining` lowest indices are kept; output in index order
   const uint32_t thr = prefix;
-  const int seg = (m + 255) / 256;
-  const int j0 = min(tid * seg, m), j1 = min(j0 + seg, m);
-  int eq = 0;
-  for (int j = j0; j < j1; ++j) eq += keys[j] == thr;
-  int total;
-  int eq_before = block_excl_scan_256(eq, tmp, &total);
-  int kept = 0;
-  {
-    int e = eq_before;
-    for (int j = j0; j < j1; ++j) {
-      uint32_t kk = keys[j];
-      kept += (kk > thr) || (kk == thr && e < remaining);
-      e += kk == thr;
-    }
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  int eq_seen = 0, pos = 0;
+  for (int j0 = 0; j0 < m; j0 += 64) {
+    const int j = j0 + lane;
+    const bool valid = j < m;
+    const uint32_t kk = valid ? keys[j] : 0u;
+    const bool is_eq = valid && kk == thr;
+    const unsigned long long beq = __builtin_amdgcn_ballot_w64(is_eq);
+    const int eq_rank = eq_seen + __builtin_popcountll(beq & lt);
+    const bool keep = valid && (kk > thr || (is_eq && eq_rank < remaining));
+    const unsigned long long bk = __builtin_amdgcn_ballot_w64(keep);
+    if (keep) out[pos + __builtin_popcountll(bk & lt)] = j;
+    pos += __builtin_popcountll(bk);
+    eq_seen += __builtin_popcountll(beq);
   }
-  int pos = block_excl_scan_256(kept, tmp, &total);
-  {
-    int e = eq_before;
-    for (int j = j0; j < j1; ++j) {
-      uint32_t kk = keys[j];
-      if ((kk > thr) || (kk == thr && e < remaining)) out[pos++] = j;
-      e += kk == thr;
-    }
-  }
-  if (tid == 0) out[need] = i;
+  if (lane == 0) out[need] = i;
 }
 
 }  // namespace sb
@@ -136,19 +140,25 @@ extern "C" int sb_select_topk(const sb_problem* p, const float* scores, int32_t*
   rc = launch_geom(g, p, ws, st);
   if (rc != SB_OK) return rc;
   Tables t = make_tables(g, p, ws);
-  dim3 grid((unsigned)g.NQB, (unsigned)g.Hs);
-  size_t smem = sizeof(uint32_t) * (size_t)(g.n_max + 1);
+  // every wavefront owns a region of n_max keys (rounded up to 64) plus 256 histogram bins; as many rows per workgroup
+  // (at most four) as fit in 64 KiB
+  const int region_words = (int)((g.n_max + 63) / 64 * 64 + 256);
+  int W = (int)(65536 / (sizeof(uint32_t) * (size_t)region_words));
+  W = W < 1 ? 1 : (W > 4 ? 4 : W);
+  const size_t smem = sizeof(uint32_t) * (size_t)region_words * W;
   if (smem > 48 * 1024) {
     static bool attr_set = false;
     if (!attr_set) {
       SB_CHECK_HIP(hipFuncSetAttribute((const void*)topk_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)(sizeof(uint32_t) * (SB_MAX_BLOCKS_PER_SEQ + 1))));
+                                       (int)(sizeof(uint32_t) * (SB_MAX_BLOCKS_PER_SEQ + 256))));
       attr_set = true;
     }
   }
+  const int64_t rows = (int64_t)g.Hs * g.NQB;
+  dim3 grid((unsigned)((rows + W - 1) / W));
   KernelTimer kt(K_TOPK, st);
-  hipLaunchKernelGGL(topk_kernel, grid, dim3(256), smem, st, scores, t.qb_off, t.sc_off, t.row_base, t.kclamp, t.qb_seq,
-                     g.NQB, g.Hs, g.nnz_unit, sel_rowptr_out, sel_idx_out);
+  hipLaunchKernelGGL(topk_kernel, grid, dim3(64 * W), smem, st, scores, t.qb_off, t.sc_off, t.row_base, t.kclamp, t.qb_seq,
+                     g.NQB, g.Hs, g.nnz_unit, region_words, sel_rowptr_out, sel_idx_out);
   SB_LAUNCH_CHECK("topk_kernel");
   return SB_OK;
 }
