@@ -180,9 +180,9 @@ size_t scores_ws_bytes(const Geo& g) {
 __global__ __launch_bounds__(1024) void geom_kernel(const int32_t* __restrict__ cu, const int32_t* __restrict__ topk, int S, int B,
                                                     int64_t NQB, int32_t* qb_off, int64_t* sc_off, int32_t* row_base,
                                                     int64_t* bm_off, int32_t* kclamp, int32_t* qb_seq) {
-  __shared__ long long sh[4][1024];
+  __shared__ long long wsum[4][16];  // per-wavefront totals of the four scanned columns
   __shared__ long long carry[4];
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (tid < 4) carry[tid] = 0;
   if (tid == 0) { qb_off[0] = 0; sc_off[0] = 0; row_base[0] = 0; bm_off[0] = 0; }
   __syncthreads();
@@ -197,23 +197,35 @@ __global__ __launch_bounds__(1024) void geom_kernel(const int32_t* __restrict__ 
       kclamp[s] = (int32_t)k;
       v[0] = n; v[1] = n * n; v[2] = k * n - k * (k - 1) / 2; v[3] = n * ((n + 31) / 32);
     }
-    for (int a = 0; a < 4; ++a) sh[a][tid] = v[a];
+    // inclusive scan of the four columns: inside each wavefront by shuffles, then over the 16 wavefront totals
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const long long t = __shfl_up(v[a], off, 64);
+        if (lane >= off) v[a] += t;
+      }
+      if (lane == 63) wsum[a][wave] = v[a];
+    }
     __syncthreads();
-    for (int off = 1; off < 1024; off <<= 1) {  // inclusive Hillis-Steele scan of the four columns
-      long long t[4];
-      for (int a = 0; a < 4; ++a) t[a] = tid >= off ? sh[a][tid - off] : 0;
-      __syncthreads();
-      for (int a = 0; a < 4; ++a) sh[a][tid] += t[a];
-      __syncthreads();
+    long long before[4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      before[a] = 0;
+      for (int w = 0; w < wave; ++w) before[a] += wsum[a][w];
     }
     if (s < S) {
-      qb_off[s + 1] = (int32_t)(carry[0] + sh[0][tid]);
-      sc_off[s + 1] = carry[1] + sh[1][tid];
-      row_base[s + 1] = (int32_t)(carry[2] + sh[2][tid]);
-      bm_off[s + 1] = carry[3] + sh[3][tid];
+      qb_off[s + 1] = (int32_t)(carry[0] + before[0] + v[0]);
+      sc_off[s + 1] = carry[1] + before[1] + v[1];
+      row_base[s + 1] = (int32_t)(carry[2] + before[2] + v[2]);
+      bm_off[s + 1] = carry[3] + before[3] + v[3];
     }
     __syncthreads();
-    if (tid < 4) carry[tid] += sh[tid][1023];
+    if (tid < 4) {
+      long long total = 0;
+      for (int w = 0; w < 16; ++w) total += wsum[tid][w];
+      carry[tid] += total;
+    }
     __syncthreads();
   }
   __threadfence_block();

@@ -234,3 +234,10 @@ def test_four_heads_per_kv_group_share_tiles(D, dtype):
     between the group's heads (ragged tails, a 1-token and an empty sequence, more than one tile per row)."""
     w = synth.small_ragged(seed=17, lens=(330, 64, 1, 0, 129, 500), Hq=8, Hkv=2, D=D, ratio=(0.3, 0.9), dtype=dtype)
     full_check(w, sb.SB_SELECT_PER_KVGROUP)
+
+
+def test_more_than_1024_sequences():
+    """More sequences than one pass of the geometry scan holds (1024): offsets carry over between passes."""
+    lens = [1 + (37 * s + 11 * (s // 7)) % 150 for s in range(1100)]
+    w = synth.small_ragged(seed=23, lens=lens, Hq=2, Hkv=1, D=64, ratio=(0.3, 1.0))
+    full_check(w, sb.SB_SELECT_PER_QHEAD)
