@@ -142,7 +142,10 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
   for (int dt = 0; dt < D / 32; ++dt) dqacc[dt] = zero16();
   bf16x8 op[NOP];  // one rotating operand set: a register is refilled for the next contraction as soon as it has been consumed
 
-  for (int t = 0; t < ntiles; ++t) {
+  // The diagonal block is always the last tile of a row: it takes its own instantiation of the tile
+  // body, so that the other tiles carry no mask selects.
+  auto tile = [&](auto diag_c, int t) __attribute__((always_inline)) {
+    constexpr bool diag = decltype(diag_c)::value;
     const bool more = t + 1 < ntiles;
     if (more && (t + 1) % kJ == 0) stage_indices(t + 1);
     wait_vmcnt<0>();
@@ -155,7 +158,6 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
 #pragma unroll
       for (int dt = 0; dt < D / 32; ++dt) { tr_a[dt][0] += dl; tr_a[dt][1] += dl; }
     }
-    const bool diag = t == ntiles - 1;
 #pragma unroll
     for (int mt = 0; mt < NMT; ++mt) {  // keys 32(mt + kh) .. +31 of the tile
       const unsigned ro = mt * 32 * ROW_B;
@@ -209,7 +211,9 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
       }
       __builtin_amdgcn_sched_group_barrier(0x008, D / 32, 0);
     }
-  }
+  };
+  for (int t = 0; t + 1 < ntiles; ++t) tile(std::false_type(), t);
+  tile(std::true_type(), ntiles - 1);
   if (KS == 2) {  // add the two key halves of every row: the kh = 1 wavefront hands its partial over
     float* xbuf = (float*)&tiles[0][0][0] + (size_t)(wave >> 2) * 2 * (16 * (D / 32) * 64) + (size_t)strip * (16 * (D / 32) * 64);
     __syncthreads();  // everyone is done with the tile buffers

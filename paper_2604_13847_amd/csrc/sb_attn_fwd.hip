@@ -431,7 +431,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void a
   float m = -__builtin_inff(), l = 0.f;
   bf16x8 op[NOP];
 
-  for (int t = 0; t < ntiles; ++t) {
+  // The diagonal block is always the last tile of a row: it takes its own instantiation of the tile
+  // body, so that the other tiles carry no mask selects.
+  auto tile = [&](auto diag_c, int t) __attribute__((always_inline)) {
+    constexpr bool diag = decltype(diag_c)::value;
     const bool more = t + 1 < ntiles;
     if (more && (t + 1) % kJ == 0) stage_indices(t + 1);
     wait_vmcnt<0>();
@@ -444,7 +447,6 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void a
 #pragma unroll
       for (int dt = 0; dt < D / 32; ++dt) { tr_a[dt][0] += dl; tr_a[dt][1] += dl; }
     }
-    const bool diag = t == ntiles - 1;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {  // keys 32mt .. 32mt+31 of the tile
 #pragma unroll
@@ -505,7 +507,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void a
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt) oacc[dt] = mfma32(op[kk * (D / 32) + dt], pb[kk], oacc[dt]);
     }
-  }
+  };
+  for (int t = 0; t + 1 < ntiles; ++t) tile(std::false_type(), t);
+  tile(std::true_type(), ntiles - 1);
 
   l += __shfl_xor(l, 32, 64);  // the two lane halves hold different keys of the same query
   if (qvalid) {
