@@ -113,8 +113,8 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
   asm volatile("" : "+v"(lse2), "+v"(dr));
   issue(0);
 
-  // LDS byte addresses of this lane's operand reads inside the current buffer's K tile, key half kh;
-  // they move to the other buffer once per tile, everything else is a compile-time offset
+  // LDS byte addresses of this lane's operand reads inside buffer 0's K tile, key half kh; the buffer
+  // and everything else is a compile-time offset
   const unsigned tiles0 = lds_offset(&tiles[0][0][0]);
   unsigned row_a[NOP], tr_a[D / 32][2];
 #pragma unroll
@@ -144,23 +144,17 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
 
   // The diagonal block is always the last tile of a row: it takes its own instantiation of the tile
   // body, so that the other tiles carry no mask selects.
-  auto tile = [&](auto diag_c, int t) __attribute__((always_inline)) {
+  auto tile = [&](auto diag_c, auto buf_c, int t) __attribute__((always_inline)) {
     constexpr bool diag = decltype(diag_c)::value;
+    constexpr unsigned BO = decltype(buf_c)::value * 2 * TILE_B;  // the tile's buffer, as an immediate offset of every LDS read
     const bool more = t + 1 < ntiles;
     if (more && (t + 1) % kJ == 0) stage_indices(t + 1);
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();  // tile t has landed for everyone; everyone is done with tile t-1
     if (more) issue(t + 1);
-    if (t > 0) {  // the operand addresses follow the tile into the other buffer
-      const int dl = (t & 1) ? 2 * TILE_B : -2 * TILE_B;
-#pragma unroll
-      for (int ks = 0; ks < NOP; ++ks) row_a[ks] += dl;
-#pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt) { tr_a[dt][0] += dl; tr_a[dt][1] += dl; }
-    }
 #pragma unroll
     for (int mt = 0; mt < NMT; ++mt) {  // keys 32(mt + kh) .. +31 of the tile
-      const unsigned ro = mt * 32 * ROW_B;
+      const unsigned ro = BO + mt * 32 * ROW_B;
 #pragma unroll
       for (int ks = 0; ks < NOP; ++ks) op[ks] = ld_row(ks, ro);  // K rows
       __builtin_amdgcn_sched_barrier(0);
@@ -179,7 +173,7 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
 #pragma unroll
       for (int ks = 0; ks < NOP; ++ks) {  // dP^T = V dO^T, refilling with the K^T operands of the dQ step
         dpacc = mfma32(op[ks], dof[ks], dpacc);
-        op[ks] = ld_tr(2 * mt + ks / (D / 32), ks % (D / 32), 0);
+        op[ks] = ld_tr(2 * mt + ks / (D / 32), ks % (D / 32), BO);
       }
 #pragma unroll
       for (int i_ = 0; i_ < NOP; ++i_) {
@@ -212,8 +206,21 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
       __builtin_amdgcn_sched_group_barrier(0x008, D / 32, 0);
     }
   };
-  for (int t = 0; t + 1 < ntiles; ++t) tile(std::false_type(), t);
-  tile(std::true_type(), ntiles - 1);
+  {  // two tiles per iteration, so that the buffer of a tile is known at compile time
+    using B0 = std::integral_constant<int, 0>;
+    using B1 = std::integral_constant<int, 1>;
+    int t = 0;
+    for (; t + 2 < ntiles; t += 2) {
+      tile(std::false_type(), B0(), t);
+      tile(std::false_type(), B1(), t + 1);
+    }
+    if (t + 2 == ntiles) {
+      tile(std::false_type(), B0(), t);
+      tile(std::true_type(), B1(), t + 1);
+    } else {
+      tile(std::true_type(), B0(), t);
+    }
+  }
   if (KS == 2) {  // add the two key halves of every row: the kh = 1 wavefront hands its partial over
     float* xbuf = (float*)&tiles[0][0][0] + (size_t)(wave >> 2) * 2 * (16 * (D / 32) * 64) + (size_t)strip * (16 * (D / 32) * 64);
     __syncthreads();  // everyone is done with the tile buffers

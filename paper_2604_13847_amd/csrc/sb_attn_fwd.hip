@@ -418,8 +418,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void a
     return *(const bf16x8 __attribute__((address_space(3)))*)(row_a[ks] + off);
   };
   // A operand of O^T += V^T P^T: row = d (32dt + lane%32), slots = keys 16kk + 8(e/4) + 4hf + e%4 of this wavefront's rows
-  auto ld_tr = [&](int kk, int dt) __attribute__((always_inline)) {
-    const unsigned o = kk * 16 * ROW_B;
+  auto ld_tr = [&](int kk, int dt, unsigned off) __attribute__((always_inline)) {
+    const unsigned o = off + kk * 16 * ROW_B;
     bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(tr_a[dt][0] + o));
     bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(tr_a[dt][1] + o));
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -433,30 +433,24 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void a
 
   // The diagonal block is always the last tile of a row: it takes its own instantiation of the tile
   // body, so that the other tiles carry no mask selects.
-  auto tile = [&](auto diag_c, int t) __attribute__((always_inline)) {
+  auto tile = [&](auto diag_c, auto buf_c, int t) __attribute__((always_inline)) {
     constexpr bool diag = decltype(diag_c)::value;
+    constexpr unsigned BO = decltype(buf_c)::value * 2 * TILE_B;  // the tile's buffer, as an immediate offset of every LDS read
     const bool more = t + 1 < ntiles;
     if (more && (t + 1) % kJ == 0) stage_indices(t + 1);
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();  // tile t has landed for everyone; everyone is done with tile t-1
     if (more) issue(t + 1);
-    if (t > 0) {  // the operand addresses follow the tile into the other buffer
-      const int dl = (t & 1) ? 2 * TILE_B : -2 * TILE_B;
-#pragma unroll
-      for (int ks = 0; ks < NOP; ++ks) row_a[ks] += dl;
-#pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt) { tr_a[dt][0] += dl; tr_a[dt][1] += dl; }
-    }
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {  // keys 32mt .. 32mt+31 of the tile
 #pragma unroll
-      for (int ks = 0; ks < NOP; ++ks) op[ks] = ld_row(ks, mt * 32 * ROW_B);  // K rows
+      for (int ks = 0; ks < NOP; ++ks) op[ks] = ld_row(ks, BO + mt * 32 * ROW_B);  // K rows
       __builtin_amdgcn_sched_barrier(0);
       f32x16 sacc = zero16();
 #pragma unroll
       for (int ks = 0; ks < NOP; ++ks) {  // S^T = K Q^T, refilling every operand register with a V^T operand
         sacc = mfma32(op[ks], qf[ks], sacc);
-        op[ks] = ld_tr(2 * mt + ks / (D / 32), ks % (D / 32));
+        op[ks] = ld_tr(2 * mt + ks / (D / 32), ks % (D / 32), BO);
       }
 #pragma unroll
       for (int i_ = 0; i_ < NOP; ++i_) {
@@ -508,8 +502,21 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void a
         for (int dt = 0; dt < D / 32; ++dt) oacc[dt] = mfma32(op[kk * (D / 32) + dt], pb[kk], oacc[dt]);
     }
   };
-  for (int t = 0; t + 1 < ntiles; ++t) tile(std::false_type(), t);
-  tile(std::true_type(), ntiles - 1);
+  {  // two tiles per iteration, so that the buffer of a tile is known at compile time
+    using B0 = std::integral_constant<int, 0>;
+    using B1 = std::integral_constant<int, 1>;
+    int t = 0;
+    for (; t + 2 < ntiles; t += 2) {
+      tile(std::false_type(), B0(), t);
+      tile(std::false_type(), B1(), t + 1);
+    }
+    if (t + 2 == ntiles) {
+      tile(std::false_type(), B0(), t);
+      tile(std::true_type(), B1(), t + 1);
+    } else {
+      tile(std::true_type(), B0(), t);
+    }
+  }
 
   l += __shfl_xor(l, 32, 64);  // the two lane halves hold different keys of the same query
   if (qvalid) {
