@@ -315,10 +315,10 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt) { dkacc[dt] = zero16(); dvacc[dt] = zero16(); }
 
-  // LDS byte addresses of this lane's operand reads inside the current buffer (everything else is a
-  // compile-time offset: rows 16 apart share the swizzle); they move to the other buffer once per tile
+  // LDS byte addresses of this lane's operand reads inside buffer 0 (the buffer and everything else is an
+  // offset: rows 16 apart share the swizzle)
   unsigned row_a[D / 16], tr_a[D / 32][2];
-  unsigned stat_a = lds_offset(&rowstat[0][0][0]) + 16 * hf;
+  const unsigned stat_a = lds_offset(&rowstat[0][0][0]) + 16 * hf;
   {
     const unsigned tiles0 = lds_offset(&tiles[0][0][0]);
 #pragma unroll
@@ -381,9 +381,9 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
   // 32qt + 8vg + 4hf + (0..3).  The rows' statistics are fetched from LDS one stage ahead (ld_stat)
   // so that no stage has to wait for them.
   f32x4 st_ls[2], st_dd[2];
-  auto ld_stat = [&](int slot, int qt, int vg) __attribute__((always_inline)) {
-    st_ls[slot] = lds_f4(stat_a + (32 * qt + 8 * vg) * 4);
-    st_dd[slot] = lds_f4(stat_a + 256 + (32 * qt + 8 * vg) * 4);
+  auto ld_stat = [&](int slot, unsigned so, int qt, int vg) __attribute__((always_inline)) {
+    st_ls[slot] = lds_f4(stat_a + so + (32 * qt + 8 * vg) * 4);
+    st_dd[slot] = lds_f4(stat_a + so + 256 + (32 * qt + 8 * vg) * 4);
   };
   auto pointwise = [&](int slot, int qt, int vg) __attribute__((always_inline)) {
 #pragma unroll
@@ -407,7 +407,7 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
   const bool per_qhead = P.mode == SB_SELECT_PER_QHEAD;
   const int nsel = per_qhead ? P.G : 1;      // bitmap columns (selection heads) of this KV head
   const int hpe = per_qhead ? 1 : P.G;       // query heads each set bit stands for
-  int tt = 0;                                // tiles processed so far: tile tt lives in buffer tt & 1
+  int tt = 0;                                // tiles of the chunk processed so far: tile tt lives in buffer tt & 1
   for (int sel0 = 0; sel0 < nsel; sel0 += 8) {                  // selection heads in groups of 8
     const int ns8 = min(8, nsel - sel0);
     for (int w0 = ((words - 1) & ~(kCW - 1)); w0 >= ((j >> 5) & ~(kCW - 1)); w0 -= kCW) {  // chunks of kCW bitmap words, last first
@@ -466,6 +466,7 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
         h = g * P.G + sel0 + (e & 7);
       };
       // ---- prologue: tiles 0 and 1 in flight, the first operands of tile 0 on their way to registers
+      tt = 0;  // every chunk starts in buffer 0 (the barrier above has drained the loads and reads of the previous one)
       {
         int i0, h0;
         entry(0, i0, h0);
@@ -485,21 +486,25 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
       // tile is spread under the matrix instructions of the next stages.  The instruction mix of every
       // stage is pinned with scheduling groups: one matrix instruction, then its share of the LDS reads
       // and of the vector arithmetic.
-      auto run_tiles = [&](auto diag_c, int tb, int te) __attribute__((always_inline)) {
-        constexpr bool DIAG = decltype(diag_c)::value;
-        for (int t = tb; t < te; ++t, ++tt) {
+      // BUF = 0 / 1: the tile's buffer is known at compile time and is an immediate offset of every LDS read;
+      // BUF = -1: it is tt & 1 and the offsets are added per tile
+      auto tile = [&](auto diag_c, auto buf_c, int t) __attribute__((always_inline)) {
+          constexpr bool DIAG = decltype(diag_c)::value;
+          constexpr int BUF = decltype(buf_c)::value;
+          const int buf = BUF >= 0 ? BUF : (tt & 1);
+          const unsigned BO = buf * BUF_B, NBO = (1 - buf) * BUF_B, SO = buf * 512;
           const int e2 = t + 2 < ntl ? (int)tl_s[ntl - 3 - t] : 0;
           // stage 0: S(queries 0..31)
-          ld_rows(opB, TILE_B);
+          ld_rows(opB, BO + TILE_B);
           sacc[0] = zero16();
 #pragma unroll
           for (int ks = 0; ks < NOP; ++ks) sacc[0] = mfma32(opA[ks], kf[ks], sacc[0]);
           SB_PIPE(1, 0);
           SB_STAGE_FENCE();
           // stage 1: dP(queries 0..31)
-          ld_rows(opA, 32 * ROW_B);
-          ld_stat(0, 0, 0);
-          ld_stat(1, 0, 1);
+          ld_rows(opA, BO + 32 * ROW_B);
+          ld_stat(0, SO, 0, 0);
+          ld_stat(1, SO, 0, 1);
           dpacc[0] = zero16();
 #pragma unroll
           for (int ks = 0; ks < NOP; ++ks) dpacc[0] = mfma32(opB[ks], vf[ks], dpacc[0]);
@@ -507,7 +512,7 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
           SB_STAGE_FENCE();
           // stage 2: S(queries 32..63) | first half of the pointwise work of queries 0..31
           if (DIAG) mask_diag(0);
-          ld_rows(opB, TILE_B + 32 * ROW_B);
+          ld_rows(opB, BO + TILE_B + 32 * ROW_B);
           sacc[1] = zero16();
 #pragma unroll
           for (int ks = 0; ks < NOP; ++ks) sacc[1] = mfma32(opA[ks], kf[ks], sacc[1]);
@@ -515,11 +520,11 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
           pointwise(1, 0, 1);
           SB_PIPE(1, 8);
           SB_STAGE_FENCE();
-          ld_stat(0, 0, 2);
-          ld_stat(1, 0, 3);
+          ld_stat(0, SO, 0, 2);
+          ld_stat(1, SO, 0, 3);
           SB_STAGE_FENCE();
           // stage 3: dP(queries 32..63) | second half
-          ld_tr(opA, TILE_B, 0);
+          ld_tr(opA, BO + TILE_B, 0);
           dpacc[1] = zero16();
 #pragma unroll
           for (int ks = 0; ks < NOP; ++ks) dpacc[1] = mfma32(opB[ks], vf[ks], dpacc[1]);
@@ -527,12 +532,12 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
           pointwise(1, 0, 3);
           SB_PIPE(2, 8);
           SB_STAGE_FENCE();
-          ld_stat(0, 1, 0);
-          ld_stat(1, 1, 1);
+          ld_stat(0, SO, 1, 0);
+          ld_stat(1, SO, 1, 1);
           SB_STAGE_FENCE();
           // stage 4: dV += P^T dO over queries 0..31 | first half of the pointwise work of queries 32..63
           if (DIAG) mask_diag(1);
-          ld_tr(opB, 0, 0);
+          ld_tr(opB, BO, 0);
 #pragma unroll
           for (int q = 0; q < 2; ++q)
 #pragma unroll
@@ -541,11 +546,11 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
           pointwise(1, 1, 1);
           SB_PIPE(2, 8);
           SB_STAGE_FENCE();
-          ld_stat(0, 1, 2);
-          ld_stat(1, 1, 3);
+          ld_stat(0, SO, 1, 2);
+          ld_stat(1, SO, 1, 3);
           SB_STAGE_FENCE();
           // stage 5: dK += dS^T Q over queries 0..31 | second half
-          ld_tr(opA, TILE_B, 2);
+          ld_tr(opA, BO + TILE_B, 2);
 #pragma unroll
           for (int q = 0; q < 2; ++q)
 #pragma unroll
@@ -555,7 +560,7 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
           SB_PIPE(2, 8);
           SB_STAGE_FENCE();
           // stage 6: dV over queries 32..63
-          ld_tr(opB, 0, 2);
+          ld_tr(opB, BO, 2);
 #pragma unroll
           for (int q = 0; q < 2; ++q)
 #pragma unroll
@@ -569,28 +574,32 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
           __builtin_amdgcn_s_barrier();
           if (t + 2 < ntl) {
             const int e = __builtin_amdgcn_readfirstlane(e2);
-            issue(tt & 1, 32 * w0 + (e >> 3), g * P.G + sel0 + (e & 7));
-          }
-          {
-            const int dl = (tt & 1) ? -BUF_B : BUF_B, ds = (tt & 1) ? -512 : 512;
-#pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) row_a[ks] += dl;
-#pragma unroll
-            for (int dt = 0; dt < D / 32; ++dt) { tr_a[dt][0] += dl; tr_a[dt][1] += dl; }
-            stat_a += ds;
+            issue(buf, 32 * w0 + (e >> 3), g * P.G + sel0 + (e & 7));
           }
           SB_STAGE_FENCE();
-          ld_rows(opA, 0);  // (after the last tile of the chunk this reads a stale buffer and is not used)
+          ld_rows(opA, NBO);  // (after the last tile of the chunk this reads a stale buffer and is not used)
 #pragma unroll
           for (int q = 0; q < 2; ++q)
 #pragma unroll
             for (int dt = 0; dt < D / 32; ++dt) dkacc[dt] = mfma32(dsa[2 + q], opB[q * (D / 32) + dt], dkacc[dt]);
           SB_PIPE(1, 0);
           SB_STAGE_FENCE();
-        }
+          ++tt;
       };
-      run_tiles(std::false_type(), 0, ntl - nd);
-      run_tiles(std::true_type(), ntl - nd, ntl);
+      {
+        using B0 = std::integral_constant<int, 0>;
+        using B1 = std::integral_constant<int, 1>;
+        using BR = std::integral_constant<int, -1>;
+        const int nn = ntl - nd;  // tiles without a mask: in pairs, the chunk starts in buffer 0
+        int t = 0;
+        for (; t + 2 <= nn; t += 2) {
+          tile(std::false_type(), B0(), t);
+          tile(std::false_type(), B1(), t + 1);
+        }
+        if (t < nn) tile(std::false_type(), B0(), t++);
+        for (; t < ntl; ++t) tile(std::true_type(), BR(), t);  // the diagonal tiles
+      }
+
     }
   }
 #undef SB_PIPE
