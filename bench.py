@@ -106,7 +106,7 @@ def main():
     # every buffer is allocated once, outside the timed region
     def raw(nbytes):
         return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=dev)
-    ws_scores, ws_sel, ws_fwd, ws_bwd = raw(lay.scores_ws_bytes), raw(lay.select_ws_bytes), raw(lay.fwd_ws_bytes), raw(lay.bwd_ws_bytes)
+    ws_scores, ws_fwd, ws_bwd = raw(lay.scores_ws_bytes), raw(lay.fwd_ws_bytes), raw(lay.bwd_ws_bytes)
     plan = raw(lay.plan_bytes)
     o, lse = torch.empty_like(q), torch.empty((w.Hq, w.T), dtype=torch.float32, device=dev)
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
@@ -119,8 +119,7 @@ def main():
     P = lambda x: C.c_void_p(x.data_ptr())
 
     def step():
-        rc = L.sb_block_scores(pb.ref(), P(q), P(k), None, P(scores), P(ws_scores), st)
-        rc |= L.sb_select_topk(pb.ref(), P(scores), P(rowptr), P(idx), P(ws_sel), st)
+        rc = L.sb_score_select(pb.ref(), P(q), P(k), None, P(scores), P(rowptr), P(idx), P(ws_scores), st)
         rc |= L.sb_plan_worklist(pb.ref(), P(rowptr), P(idx), P(plan), st)
         rc |= L.sb_sparse_attn_fwd(pb.ref(), P(q), P(k), P(v), P(rowptr), P(idx), P(plan), P(o), P(lse), P(ws_fwd), st)
         rc |= L.sb_sparse_attn_bwd(pb.ref(), P(q), P(k), P(v), P(o), P(lse), P(do), P(rowptr), P(idx), P(plan),

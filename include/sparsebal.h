@@ -112,6 +112,13 @@ int sb_block_scores(const sb_problem *p, const void *q, const void *k, float *kb
 int sb_select_topk(const sb_problem *p, const float *scores, int32_t *sel_rowptr_out, int32_t *sel_idx_out,
                    void *ws, void *stream);
 
+/* sb_block_scores followed by sb_select_topk on the scores it wrote, in one call that computes the
+ * sequence geometry once (paper section 2.2: the indexer and the Top-K selection are one step of the
+ * method; the scores stay available in scores_out for the budget controller below).  Arguments as for
+ * the two calls; ws: dev, scores_ws_bytes.  Results are identical to calling the two separately. */
+int sb_score_select(const sb_problem *p, const void *q, const void *k, float *kbar_out, float *scores_out,
+                    int32_t *sel_rowptr_out, int32_t *sel_idx_out, void *ws, void *stream);
+
 /* Work plan for the attention kernels: query-major work items (s,hs,i) ordered by decreasing
  * selected-block count (longest first, as in balanced partitioning by workload weight, paper
  * section 4.3), the key-major transpose of the selection (for every (s,hs,j) the set of query

@@ -20,7 +20,7 @@ SB_BF16, SB_F32 = 0, 1
 SB_SELECT_PER_QHEAD, SB_SELECT_PER_KVGROUP = 0, 1
 SB_CU_SLOTS = 512
 
-EXPORTS = ["sb_get_layout", "sb_keep_ratio_to_topk", "sb_sel_rowptr_host", "sb_block_scores", "sb_select_topk",
+EXPORTS = ["sb_get_layout", "sb_keep_ratio_to_topk", "sb_sel_rowptr_host", "sb_block_scores", "sb_select_topk", "sb_score_select",
            "sb_plan_worklist", "sb_sparse_attn_fwd", "sb_sparse_attn_bwd", "sb_score_coverage", "sb_perf_predict", "sb_perf_align", "sb_dst_tune",
            "sb_spar_update", "sb_spar_predict", "sb_balanced_partition", "sb_sab_batches",
            "sb_set_instrumentation", "sb_read_cu_busy", "sb_read_kernel_times",
@@ -147,6 +147,17 @@ def sb_select_topk(pb: Problem, scores, ws=None):
     ws = ws if ws is not None else _bytes(lay.select_ws_bytes, scores.device)
     _check(lib().sb_select_topk(pb.ref(), _ptr(scores), _ptr(rowptr), _ptr(idx), _ptr(ws), _stream()))
     return rowptr, idx
+
+
+def sb_score_select(pb: Problem, q, k, ws=None):
+    """Scores and selection in one call; returns (scores, sel_rowptr, sel_idx)."""
+    lay = pb.layout
+    scores = torch.empty(max(lay.scores_elems, 1), dtype=torch.float32, device=q.device)
+    rowptr = torch.empty(lay.sel_rows + 1, dtype=torch.int32, device=q.device)
+    idx = torch.empty(max(lay.sel_nnz, 1), dtype=torch.int32, device=q.device)
+    ws = ws if ws is not None else _bytes(lay.scores_ws_bytes, q.device)
+    _check(lib().sb_score_select(pb.ref(), _ptr(q), _ptr(k), None, _ptr(scores), _ptr(rowptr), _ptr(idx), _ptr(ws), _stream()))
+    return scores, rowptr, idx
 
 
 def sb_plan_worklist(pb: Problem, sel_rowptr, sel_idx, plan=None):

@@ -126,20 +126,9 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ sco
 
 using namespace sb;
 
-extern "C" int sb_select_topk(const sb_problem* p, const float* scores, int32_t* sel_rowptr_out, int32_t* sel_idx_out,
-                              void* ws, void* stream) {
-  Geo g;
-  int rc = make_geo(p, &g);
-  if (rc != SB_OK) return rc;
-  if (!sel_rowptr_out) { set_error("null sel_rowptr_out"); return SB_ERR_INVALID_ARG; }
-  hipStream_t st = (hipStream_t)stream;
-  if (g.S == 0 || g.T == 0 || g.NQB == 0) {
-    return fill_zero(sel_rowptr_out, sizeof(int32_t), st);
-  }
-  if (!scores || !sel_idx_out || !ws) { set_error("null scores, sel_idx_out or ws"); return SB_ERR_INVALID_ARG; }
-  rc = launch_geom(g, p, ws, st);
-  if (rc != SB_OK) return rc;
-  Tables t = make_tables(g, p, ws);
+// launches the selection on tables that are already in device memory
+static int select_launch(const Geo& g, const Tables& t, const float* scores, int32_t* sel_rowptr_out, int32_t* sel_idx_out,
+                         hipStream_t st) {
   // every wavefront owns a region of n_max keys (rounded up to 64) plus 256 histogram bins; as many rows per workgroup
   // (at most four) as fit in 64 KiB
   const int region_words = (int)((g.n_max + 63) / 64 * 64 + 256);
@@ -161,4 +150,36 @@ extern "C" int sb_select_topk(const sb_problem* p, const float* scores, int32_t*
                      g.NQB, g.Hs, g.nnz_unit, region_words, sel_rowptr_out, sel_idx_out);
   SB_LAUNCH_CHECK("topk_kernel");
   return SB_OK;
+}
+
+extern "C" int sb_select_topk(const sb_problem* p, const float* scores, int32_t* sel_rowptr_out, int32_t* sel_idx_out,
+                              void* ws, void* stream) {
+  Geo g;
+  int rc = make_geo(p, &g);
+  if (rc != SB_OK) return rc;
+  if (!sel_rowptr_out) { set_error("null sel_rowptr_out"); return SB_ERR_INVALID_ARG; }
+  hipStream_t st = (hipStream_t)stream;
+  if (g.S == 0 || g.T == 0 || g.NQB == 0) {
+    return fill_zero(sel_rowptr_out, sizeof(int32_t), st);
+  }
+  if (!scores || !sel_idx_out || !ws) { set_error("null scores, sel_idx_out or ws"); return SB_ERR_INVALID_ARG; }
+  rc = launch_geom(g, p, ws, st);
+  if (rc != SB_OK) return rc;
+  return select_launch(g, make_tables(g, p, ws), scores, sel_rowptr_out, sel_idx_out, st);
+}
+
+extern "C" int sb_score_select(const sb_problem* p, const void* q, const void* k, float* kbar_out, float* scores_out,
+                               int32_t* sel_rowptr_out, int32_t* sel_idx_out, void* ws, void* stream) {
+  Geo g;
+  int rc = make_geo(p, &g);
+  if (rc != SB_OK) return rc;
+  if (!sel_rowptr_out) { set_error("null sel_rowptr_out"); return SB_ERR_INVALID_ARG; }
+  hipStream_t st = (hipStream_t)stream;
+  if (g.S == 0 || g.T == 0 || g.NQB == 0) {
+    return fill_zero(sel_rowptr_out, sizeof(int32_t), st);
+  }
+  if (!sel_idx_out) { set_error("null sel_idx_out"); return SB_ERR_INVALID_ARG; }
+  rc = sb_block_scores(p, q, k, kbar_out, scores_out, ws, stream);  // leaves the geometry tables at the start of ws
+  if (rc != SB_OK) return rc;
+  return select_launch(g, make_tables(g, p, ws), scores_out, sel_rowptr_out, sel_idx_out, st);
 }

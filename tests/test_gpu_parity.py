@@ -241,3 +241,18 @@ def test_more_than_1024_sequences():
     lens = [1 + (37 * s + 11 * (s // 7)) % 150 for s in range(1100)]
     w = synth.small_ragged(seed=23, lens=lens, Hq=2, Hkv=1, D=64, ratio=(0.3, 1.0))
     full_check(w, sb.SB_SELECT_PER_QHEAD)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_score_select_in_one_call(mode):
+    """sb_score_select = sb_block_scores + sb_select_topk: same bits as the two calls, and the selection is the checker's
+    on the scores it returned."""
+    w = synth.small_ragged(seed=31, lens=(700, 64, 1, 0, 130, 1500), Hq=8, Hkv=2, D=128, ratio=(0.2, 0.9))
+    r = Run(w, mode, do_bwd=False)
+    scores, rowptr, idx = sb.sb_score_select(r.pb, r.q, r.k)
+    torch.cuda.synchronize()
+    n = r.pb.layout.scores_elems
+    assert torch.equal(scores[:n].view(torch.int32), r.scores[:n].view(torch.int32))
+    assert torch.equal(rowptr, r.rowptr) and torch.equal(idx[: int(r.rowptr_h[-1])], r.idx[: int(r.rowptr_h[-1])])
+    rp, ix = orc.select_topk(r.opb, scores.cpu().numpy()[:n], r.topk)
+    assert np.array_equal(rp, rowptr.cpu().numpy()) and np.array_equal(ix, idx.cpu().numpy()[: int(rp[-1])])
