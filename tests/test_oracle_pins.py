@@ -184,6 +184,8 @@ def test_full_budget_is_dense_causal_attention(mode):
     (8, 64, [100, 9], 4, 2, 1, [4, 2]),
     (64, 4, [200], 3, 1, 1, [2]),
     (64, 64, [200, 65], 2, 2, 0, [3, 1]),
+    (128, 64, [300, 130, 128], 2, 1, 0, [2, 1, 1]),     # selection blocks larger than the kernels' 64-row tiles
+    (256, 16, [700, 257], 4, 2, 1, [2, 2]),
 ])
 def test_sparse_matches_bruteforce_mask(B, D, lens, Hq, Hkv, mode, topk):
     pb, Q, K, V, dO = make(lens, Hq, Hkv, D, B, mode, seed=13)
