@@ -146,12 +146,22 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
   // body, so that the other tiles carry no mask selects.
   auto tile = [&](auto diag_c, auto buf_c, int t) __attribute__((always_inline)) {
     constexpr bool diag = decltype(diag_c)::value;
-    constexpr unsigned BO = decltype(buf_c)::value * 2 * TILE_B;  // the tile's buffer, as an immediate offset of every LDS read
+    // BUF = 0 / 1: the tile's buffer is an immediate offset of every LDS read; BUF = -1: the operand addresses are
+    // moved to the other buffer after every tile
+    constexpr int BUF = decltype(buf_c)::value;
+    constexpr unsigned BO = BUF > 0 ? 2 * TILE_B : 0;
     const bool more = t + 1 < ntiles;
     if (more && (t + 1) % kJ == 0) stage_indices(t + 1);
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();  // tile t has landed for everyone; everyone is done with tile t-1
     if (more) issue(t + 1);
+    if (BUF < 0 && t > 0) {
+      const int dl = (t & 1) ? 2 * TILE_B : -2 * TILE_B;
+#pragma unroll
+      for (int ks = 0; ks < NOP; ++ks) row_a[ks] += dl;
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt) { tr_a[dt][0] += dl; tr_a[dt][1] += dl; }
+    }
 #pragma unroll
     for (int mt = 0; mt < NMT; ++mt) {  // keys 32(mt + kh) .. +31 of the tile
       const unsigned ro = BO + mt * 32 * ROW_B;
@@ -206,7 +216,7 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
       __builtin_amdgcn_sched_group_barrier(0x008, D / 32, 0);
     }
   };
-  {  // two tiles per iteration, so that the buffer of a tile is known at compile time
+  if (KS == 2) {  // two tiles per iteration, so that the buffer of a tile is known at compile time
     using B0 = std::integral_constant<int, 0>;
     using B1 = std::integral_constant<int, 1>;
     int t = 0;
@@ -220,6 +230,10 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
     } else {
       tile(std::true_type(), B0(), t);
     }
+  } else {  // a wavefront that computes both key halves has twice the tile body: the copies would not fit the register budget
+    using BR = std::integral_constant<int, -1>;
+    for (int t = 0; t + 1 < ntiles; ++t) tile(std::false_type(), BR(), t);
+    tile(std::true_type(), BR(), ntiles - 1);
   }
   if (KS == 2) {  // add the two key halves of every row: the kh = 1 wavefront hands its partial over
     float* xbuf = (float*)&tiles[0][0][0] + (size_t)(wave >> 2) * 2 * (16 * (D / 32) * 64) + (size_t)strip * (16 * (D / 32) * 64);

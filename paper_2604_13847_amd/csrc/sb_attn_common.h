@@ -159,6 +159,9 @@ struct TileLoader {
   static constexpr int RPI = 64 / C;   // rows covered by one wavefront-wide load
   static constexpr int LPT = (D / 8) / NW;  // loads per loader wavefront per tile
   static_assert(LPT >= 1 && LPT * NW * RPI == 64, "the loader wavefronts must cover the 64 rows exactly");
+  // Two consecutive loads of a wavefront land NW KiB apart in LDS: when that fits the instruction's immediate offset
+  // they share one M0 value (the offset moves both the global and the LDS address; voff is pre-biased for it).
+  static constexpr bool kPair = NW * 1024 < 4096 && LPT % 2 == 0;
   unsigned voff[LPT];
   int rl, pc;  // row within a load's group of RPI rows, 16-byte chunk of this lane
   int wave;
@@ -170,6 +173,7 @@ struct TileLoader {
     for (int a = 0; a < LPT; ++a) {
       const int r = ((wave & (NW - 1)) + NW * a) * RPI + rl;
       voff[a] = (unsigned)(r * H * D * 2 + 16 * (pc ^ chunk_swizzle<D>(r)));
+      if (kPair && (a & 1)) voff[a] -= NW * 1024;  // issued with an immediate offset that moves the global address too
     }
   }
   // Issue the copy of rows row0 .. row0+63 (head h) of `src` into `slot`.  Rows >= valid repeat the
@@ -186,10 +190,23 @@ struct TileLoader {
       const unsigned t_hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(tv >> 32));
       const unsigned t_lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(tv & 0xffffffffull));
       const unsigned long long ts = ((unsigned long long)t_hi << 32) | (unsigned long long)t_lo;
+      // The base is copied by a scalar instruction first: a scalar register written by a vector instruction
+      // (readfirstlane) must not be read by a vector-memory instruction within 5 wait states, while scalar reads of
+      // it are interlocked.  M0 needs one wait state (s_nop 0) before the load that uses it.
+      unsigned long long sbase;
+      if (kPair) {
 #pragma unroll
-      for (int a = 0; a < LPT; ++a)
-        asm volatile("s_mov_b32 m0, %2\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %0, %1"
-                     : : "v"(voff[a]), "s"(ts), "s"(base + ((wave & (NW - 1)) + NW * a) * 1024) : "memory", "m0");
+        for (int a = 0; a < LPT; a += 2)
+          asm volatile("s_mov_b64 %0, %4\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\t"
+                       "global_load_lds_dwordx4 %1, %0\n\t"
+                       "global_load_lds_dwordx4 %2, %0 offset:%5"
+                       : "=&s"(sbase) : "v"(voff[a]), "v"(voff[a + 1]), "s"(base + ((wave & (NW - 1)) + NW * a) * 1024), "s"(ts), "n"(NW * 1024) : "memory", "m0");
+      } else {
+#pragma unroll
+        for (int a = 0; a < LPT; ++a)
+          asm volatile("s_mov_b64 %0, %3\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0"
+                       : "=&s"(sbase) : "v"(voff[a]), "s"(base + ((wave & (NW - 1)) + NW * a) * 1024), "s"(ts) : "memory", "m0");
+      }
     } else {
 #pragma unroll
       for (int a = 0; a < LPT; ++a) {  // ragged tile (rare): the lane offsets are recomputed instead of being kept in registers
