@@ -150,18 +150,19 @@ __device__ inline void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
-// Per-lane byte offsets (from the tile's first row, head h) of the D/16 loads a loader wavefront
-// issues for a tile: load a covers tile rows (wave + 2a)*RPI .. +RPI-1.  They depend only on the
-// lane and on the tensor's row pitch, so they are computed once per kernel.
+// Per-lane byte offsets (from the tile's first row, head h) of the loads a loader wavefront issues
+// for a tile: wavefront w takes the LPT consecutive KiB (LPT * w + a) of the tile, a = 0 .. LPT-1, i.e.
+// tile rows (LPT * w + a) * RPI .. +RPI-1.  The offsets depend only on the lane and on the tensor's row
+// pitch, so they are computed once per kernel.
 template <int D, int NW = 2>  // NW: wavefronts (0 .. NW-1 of the workgroup) that share the loads of a tile
 struct TileLoader {
   static constexpr int C = D / 8;      // 16-byte chunks per row
   static constexpr int RPI = 64 / C;   // rows covered by one wavefront-wide load
   static constexpr int LPT = (D / 8) / NW;  // loads per loader wavefront per tile
   static_assert(LPT >= 1 && LPT * NW * RPI == 64, "the loader wavefronts must cover the 64 rows exactly");
-  // Two consecutive loads of a wavefront land NW KiB apart in LDS: when that fits the instruction's immediate offset
-  // they share one M0 value (the offset moves both the global and the LDS address; voff is pre-biased for it).
-  static constexpr bool kPair = NW * 1024 < 4096 && LPT % 2 == 0;
+  // Consecutive loads of a wavefront land 1 KiB apart in LDS, so up to four of them share one M0 value: the
+  // instruction's immediate offset moves both the global and the LDS address, and voff is pre-biased for it.
+  static constexpr int GRP = LPT % 4 == 0 ? 4 : (LPT % 2 == 0 ? 2 : 1);
   unsigned voff[LPT];
   int rl, pc;  // row within a load's group of RPI rows, 16-byte chunk of this lane
   int wave;
@@ -171,9 +172,8 @@ struct TileLoader {
     pc = lane % C;
 #pragma unroll
     for (int a = 0; a < LPT; ++a) {
-      const int r = ((wave & (NW - 1)) + NW * a) * RPI + rl;
-      voff[a] = (unsigned)(r * H * D * 2 + 16 * (pc ^ chunk_swizzle<D>(r)));
-      if (kPair && (a & 1)) voff[a] -= NW * 1024;  // issued with an immediate offset that moves the global address too
+      const int r = (LPT * (wave & (NW - 1)) + a) * RPI + rl;
+      voff[a] = (unsigned)(r * H * D * 2 + 16 * (pc ^ chunk_swizzle<D>(r))) - 1024u * (a % GRP);
     }
   }
   // Issue the copy of rows row0 .. row0+63 (head h) of `src` into `slot`.  Rows >= valid repeat the
@@ -182,7 +182,7 @@ struct TileLoader {
   // precomputed lane offsets, so no vector arithmetic is spent per load.
   __device__ inline void issue(bf16* slot, const bf16* src, int64_t row0, int valid, int H, int h) const {
     if (wave >= NW) return;
-    const unsigned base = lds_offset(slot);
+    const unsigned base = lds_offset(slot) + LPT * (wave & (NW - 1)) * 1024;  // this wavefront's part of the tile
     const char* tile = (const char*)(src + (row0 * H + h) * D);
     if (valid >= 64) {
       const unsigned long long tv = (unsigned long long)tile;  // wave-uniform: move it to scalar registers
@@ -194,24 +194,29 @@ struct TileLoader {
       // (readfirstlane) must not be read by a vector-memory instruction within 5 wait states, while scalar reads of
       // it are interlocked.  M0 needs one wait state (s_nop 0) before the load that uses it.
       unsigned long long sbase;
-      if (kPair) {
 #pragma unroll
-        for (int a = 0; a < LPT; a += 2)
+      for (int a = 0; a < LPT; a += GRP) {
+        if (GRP == 4)
+          asm volatile("s_mov_b64 %0, %6\n\ts_mov_b32 m0, %5\n\ts_nop 0\n\t"
+                       "global_load_lds_dwordx4 %1, %0\n\t"
+                       "global_load_lds_dwordx4 %2, %0 offset:1024\n\t"
+                       "global_load_lds_dwordx4 %3, %0 offset:2048\n\t"
+                       "global_load_lds_dwordx4 %4, %0 offset:3072"
+                       : "=&s"(sbase) : "v"(voff[a]), "v"(voff[a + 1]), "v"(voff[a + 2]), "v"(voff[a + 3]), "s"(base + a * 1024), "s"(ts) : "memory", "m0");
+        else if (GRP == 2)
           asm volatile("s_mov_b64 %0, %4\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\t"
                        "global_load_lds_dwordx4 %1, %0\n\t"
-                       "global_load_lds_dwordx4 %2, %0 offset:%5"
-                       : "=&s"(sbase) : "v"(voff[a]), "v"(voff[a + 1]), "s"(base + ((wave & (NW - 1)) + NW * a) * 1024), "s"(ts), "n"(NW * 1024) : "memory", "m0");
-      } else {
-#pragma unroll
-        for (int a = 0; a < LPT; ++a)
+                       "global_load_lds_dwordx4 %2, %0 offset:1024"
+                       : "=&s"(sbase) : "v"(voff[a]), "v"(voff[a + 1]), "s"(base + a * 1024), "s"(ts) : "memory", "m0");
+        else
           asm volatile("s_mov_b64 %0, %3\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0"
-                       : "=&s"(sbase) : "v"(voff[a]), "s"(base + ((wave & (NW - 1)) + NW * a) * 1024), "s"(ts) : "memory", "m0");
+                       : "=&s"(sbase) : "v"(voff[a]), "s"(base + a * 1024), "s"(ts) : "memory", "m0");
       }
     } else {
 #pragma unroll
       for (int a = 0; a < LPT; ++a) {  // ragged tile (rare): the lane offsets are recomputed instead of being kept in registers
-        const int r = ((wave & (NW - 1)) + NW * a) * RPI + rl;
-        dma16(tile + (int64_t)min(r, valid - 1) * H * D * 2 + 16 * (pc ^ chunk_swizzle<D>(r)), base + ((wave & (NW - 1)) + NW * a) * 1024);
+        const int r = (LPT * (wave & (NW - 1)) + a) * RPI + rl;
+        dma16(tile + (int64_t)min(r, valid - 1) * H * D * 2 + 16 * (pc ^ chunk_swizzle<D>(r)), base + a * 1024);
       }
     }
   }
