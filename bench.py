@@ -21,7 +21,7 @@ import numpy as np  # noqa: E402
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 # HBM bytes per launch of the attention kernels on cfg2 / per_qhead from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
 # (scaled as described in profiles/attn_kernels_cfg2_per_qhead_hbm_traffic.txt); None for other workloads.
-MEASURED_TRAFFIC_BYTES = {("cfg2", "per_qhead"): {"fwd": 1.003e9 + 0.273e9, "bwd_dq": 1.975e9 + 0.277e9, "bwd_dkv": 8.974e9 + 0.135e9}}
+MEASURED_TRAFFIC_BYTES = {("cfg2", "per_qhead"): {"fwd": 1.003e9 + 0.273e9, "bwd_dq": 1.982e9 + 0.277e9, "bwd_dkv": 8.940e9 + 0.135e9}}
 
 
 def make_workload(name, seed):
