@@ -258,10 +258,12 @@ def test_score_select_in_one_call(mode):
     assert np.array_equal(rp, rowptr.cpu().numpy()) and np.array_equal(ix, idx.cpu().numpy()[: int(rp[-1])])
 
 
-def test_more_than_8192_blocks_in_one_sequence():
+@pytest.mark.parametrize("nblk", [8200, 12500])
+def test_more_than_8192_blocks_in_one_sequence(nblk):
     """A sequence of 8200 blocks (524 800 tokens): more columns than one pass of the plan's transpose holds, one row per
-    workgroup in the selection, 129 row tiles in the score kernel."""
-    w = synth.Workload("long1", [64 * 8199 + 5, 70], 1, 1, 64, keep_ratio=[0.0002, 1.0], seed=29)   # k = 2 and 2
+    workgroup in the selection, 129 row tiles in the score kernel.  With 12500 blocks the selection's LDS region also
+    exceeds the default dynamic limit of 48 KiB."""
+    w = synth.Workload("long1", [64 * (nblk - 1) + 5, 70], 1, 1, 64, keep_ratio=[0.0002, 1.0], seed=29)   # k = 2 or 3, and 2
     r = Run(w, sb.SB_SELECT_PER_QHEAD)
     sc = check_scores(r)
     check_selection(r, sc)
