@@ -51,7 +51,7 @@ def measure(sb, torch, synth, L, k, Hq, Hkv, D, reps=5):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--out", default=os.path.join(ROOT, "gpurun_out", "latency_table.json"))
+    ap.add_argument("--out", default="latency_table.json")
     ap.add_argument("--heads", type=int, nargs=2, default=[32, 8])
     ap.add_argument("--dim", type=int, default=128)
     ap.add_argument("--check", action="store_true", help="also measure points between the buckets and report the prediction error")
