@@ -288,11 +288,8 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
 // down to the diagonal, all query heads of the KV group at one query block before the next:
 // concurrent columns of one KV head (same XCD) start at the same query block, advance at a similar
 // pace and so ask for the same Q/dO tiles at about the same time and meet them in that XCD's L2.
-// With selection blocks larger than a tile (NP = 2) a workgroup of four wavefronts owns two adjacent key
-// tiles of one selection block: apart from the diagonal block both are kept by exactly the same query
-// tiles, so they share every Q/dO tile load and walk the tile list of the first of the two.
-template <int D, bool OUT_F32, int NP>
-__global__ __launch_bounds__(128 * NP) __attribute__((amdgpu_waves_per_eu(1))) void attn_bwd_dkv_kernel(AttnParams P) {
+template <int D, bool OUT_F32>
+__global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void attn_bwd_dkv_kernel(AttnParams P) {
   constexpr int TILE_B = 64 * D * 2;  // bytes of one Q or dO tile
   constexpr int BUF_B = 2 * TILE_B;   // bytes of one buffer (Q tile, dO tile)
   constexpr int ROW_B = D * 2;
@@ -306,18 +303,15 @@ __global__ __launch_bounds__(128 * NP) __attribute__((amdgpu_waves_per_eu(1))) v
   timer.start(P);
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-  const int wv = wave & 1;                    // 32-key half of the key tile
-  const int pair = NP == 2 ? wave >> 1 : 0;   // which of the workgroup's key tiles
-  const int64_t col = P.work[blockIdx.x];  // g * NQB + global index of the (first) key tile
+  const int64_t col = P.work[blockIdx.x];  // g * NQB + global block index
   const int g = (int)(col / P.NQB);
   const int qbj = (int)(col - (int64_t)g * P.NQB);
   const int s = P.qb_seq[qbj];
-  const int j0 = qbj - P.qb_off[s];
-  const int j = j0 + pair;  // with NP = 2 the second tile may lie past the end of the sequence: then it has no valid key
+  const int j = qbj - P.qb_off[s];
   const int n = P.qb_off[s + 1] - P.qb_off[s];
   const int64_t seq0 = P.cu[s];
   const int L = P.cu[s + 1] - P.cu[s];
-  const int kloc = wv * 32 + l32;
+  const int kloc = wave * 32 + l32;
   const bool kvalid = j * 64 + kloc < L;
   const int64_t tk = seq0 + j * 64 + kloc;
 
@@ -373,33 +367,29 @@ __global__ __launch_bounds__(128 * NP) __attribute__((amdgpu_waves_per_eu(1))) v
       }
   };
 
-  TileLoader<D, 2 * NP> loader;  // all wavefronts of the workgroup share the tile loads
+  TileLoader<D> loader;
   loader.init(P.Hq, wave, lane);
-  constexpr int kLoadsPerTile = 2 * TileLoader<D, 2 * NP>::LPT + 1;  // asynchronous loads one wavefront issues per tile
+  constexpr int kLoadsPerTile = 2 * TileLoader<D>::LPT + 1;  // asynchronous loads one wavefront issues per tile
   auto issue = [&](int buf, int i, int h) __attribute__((always_inline)) {
     const int64_t q0 = seq0 + (int64_t)i * 64;
     const int qv = min(64, L - i * 64);
     loader.issue(tiles[buf][0], P.q, q0, qv, P.Hq, h);
     loader.issue(tiles[buf][1], P.d_o, q0, qv, P.Hq, h);
-    // 64 LSE and 64 Dr values: one 4-byte load per lane, even wavefronts take LSE and odd ones Dr (with four
-    // wavefronts two write the same values to the same place, which keeps the load count per wavefront uniform)
+    // 64 LSE and 64 Dr values: one 4-byte load per lane, wavefront 0 takes LSE and wavefront 1 Dr
     // (rows past the end of the sequence read the +inf stored behind the LSE array: their P becomes 0)
-    const float* src = wv == 0 ? (lane < qv ? P.lse2 + (int64_t)h * P.T + q0 + lane : P.lse2 + (int64_t)P.Hq * P.T)
-                               : P.drow + (int64_t)h * P.T + q0 + min(lane, qv - 1);
-    dma4(src, lds_offset(rowstat[buf][wv]));
+    const float* src = wave == 0 ? (lane < qv ? P.lse2 + (int64_t)h * P.T + q0 + lane : P.lse2 + (int64_t)P.Hq * P.T)
+                                 : P.drow + (int64_t)h * P.T + q0 + min(lane, qv - 1);
+    dma4(src, lds_offset(rowstat[buf][wave]));
   };
 
   f32x16 sacc[2], dpacc[2];
   bf16x8 pa[4], dsa[4];
   bf16x8 opA[NOP], opB[NOP];
-  // causal mask of a tile of the diagonal block (raw scores of queries 32qt .. 32qt+31); kq = this lane's key
-  // position relative to the first query of the tile (the key's own position when the tile is the key tile itself,
-  // negative for an earlier key tile of the block, 64 or more for a later one, whose keys are all hidden)
-  int kq = kloc;
+  // causal mask inside the diagonal tile (raw scores of queries 32qt .. 32qt+31)
   auto mask_diag = [&](int qt) __attribute__((always_inline)) {
 #pragma unroll
     for (int v = 0; v < 16; ++v)
-      if (kq > 32 * qt + c_row(v, hf)) sacc[qt][v] = -__builtin_inff();
+      if (kloc > 32 * qt + c_row(v, hf)) sacc[qt][v] = -__builtin_inff();
   };
   // P = exp2(S c - lse2), dS = P (dP - Dr), both to bf16, for registers 4vg .. 4vg+3 = query rows
   // 32qt + 8vg + 4hf + (0..3).  The rows' statistics are fetched from LDS one stage ahead (ld_stat)
@@ -434,16 +424,16 @@ __global__ __launch_bounds__(128 * NP) __attribute__((amdgpu_waves_per_eu(1))) v
   int tt = 0;                                // tiles of the chunk processed so far: tile tt lives in buffer tt & 1
   for (int sel0 = 0; sel0 < nsel; sel0 += 8) {                  // selection heads in groups of 8
     const int ns8 = min(8, nsel - sel0);
-    for (int w0 = ((words - 1) & ~(kCW - 1)); w0 >= ((j0 >> 5) & ~(kCW - 1)); w0 -= kCW) {  // chunks of kCW bitmap words, last first
+    for (int w0 = ((words - 1) & ~(kCW - 1)); w0 >= ((j >> 5) & ~(kCW - 1)); w0 -= kCW) {  // chunks of kCW bitmap words, last first
       const int wn = min(kCW, words - w0);
       // ---- the chunk's tile list: entry = (query block - 32 w0) * 8 + head, ordered by query block, then head.
       // The list is walked backwards (last query block first): every column of a sequence then starts at
       // the same query block and, selecting at a similar density, stays close to its neighbours.
       __syncthreads();
-      for (int a = tid; a < ns8 * kCW; a += 128 * NP) {
+      for (int a = tid; a < ns8 * kCW; a += 128) {
         const int sel = a / kCW, w = a % kCW;
         const int hs = per_qhead ? g * P.G + sel0 + sel : g;
-        bm_s[sel][w] = w < wn ? P.bitmap[(int64_t)P.Hs * P.bm_off[s] + ((int64_t)hs * n + j0) * words + w0 + w] : 0u;
+        bm_s[sel][w] = w < wn ? P.bitmap[(int64_t)P.Hs * P.bm_off[s] + ((int64_t)hs * n + j) * words + w0 + w] : 0u;
       }
       __syncthreads();
       if (tid < 64) {  // lane w counts the tiles of word w, a wavefront scan turns counts into list positions
@@ -476,13 +466,12 @@ __global__ __launch_bounds__(128 * NP) __attribute__((amdgpu_waves_per_eu(1))) v
       __syncthreads();
       const int ntl = __builtin_amdgcn_readfirstlane(ntl_s);
       if (ntl == 0) continue;
-      // the tiles that need the mask (query tile = one of the workgroup's key tiles) are the first of the list, i.e. the
-      // last to be processed: count them
+      // the diagonal tiles (query block j itself) are the first of the list, i.e. the last to be processed: count them
       int nd = 0;
-      for (int jd = j0; jd < j0 + NP; ++jd)
-        if (jd >= 32 * w0 && jd < 32 * (w0 + kCW))
-          for (int sel = 0; sel < ns8; ++sel) nd += (int)((bm_s[sel][(jd >> 5) - w0] >> (jd & 31)) & 1u) * hpe;
-      nd = __builtin_amdgcn_readfirstlane(nd);
+      if (j >= 32 * w0 && j < 32 * (w0 + kCW)) {
+        for (int sel = 0; sel < ns8; ++sel) nd += (int)((bm_s[sel][(j >> 5) - w0] >> (j & 31)) & 1u) * hpe;
+        nd = __builtin_amdgcn_readfirstlane(nd);
+      }
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) asm volatile("" : "+v"(kf[ks]), "+v"(vf[ks]));
       auto entry = [&](int t, int& i, int& h) __attribute__((always_inline)) {
@@ -519,7 +508,6 @@ __global__ __launch_bounds__(128 * NP) __attribute__((amdgpu_waves_per_eu(1))) v
           const int buf = BUF >= 0 ? BUF : (tt & 1);
           const unsigned BO = buf * BUF_B, NBO = (1 - buf) * BUF_B, SO = buf * 512;
           const int e2 = t + 2 < ntl ? (int)tl_s[ntl - 3 - t] : 0;
-          if (DIAG) kq = kloc + (j - (32 * w0 + (__builtin_amdgcn_readfirstlane((int)tl_s[ntl - 1 - t]) >> 3))) * 64;
           // stage 0: S(queries 0..31)
           ld_rows(opB, BO + TILE_B);
           sacc[0] = zero16();
@@ -635,7 +623,7 @@ __global__ __launch_bounds__(128 * NP) __attribute__((amdgpu_waves_per_eu(1))) v
   for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int kr = wv * 32 + c_row(v, hf);
+      const int kr = wave * 32 + c_row(v, hf);
       if (j * 64 + kr < L) {
         const int64_t off = ((seq0 + j * 64 + kr) * P.Hkv + g) * D + 32 * dt + l32;
         if (OUT_F32) {
@@ -669,11 +657,10 @@ static int launch_bwd(const Geo& g, const AttnParams& P, hipStream_t st) {
 }
 
 template <int D, bool F32>
-static int launch_dkv(const Geo& g, const AttnParams& P, int64_t n_work, int np, hipStream_t st) {
-  dim3 grid((unsigned)n_work);
+static int launch_dkv(const Geo& g, const AttnParams& P, hipStream_t st) {
+  dim3 grid((unsigned)(g.Hkv * g.NQB)), block(128);
   KernelTimer kt(K_BWD_DKV, st);
-  if (np == 2) hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, F32, 2>), grid, dim3(256), 0, st, P);
-  else hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, F32, 1>), grid, dim3(128), 0, st, P);
+  hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, F32>), grid, block, 0, st, P);
   SB_LAUNCH_CHECK("attn_bwd_dkv_kernel");
   return SB_OK;
 }
@@ -729,21 +716,17 @@ extern "C" int sb_sparse_attn_bwd(const sb_problem* p, const void* q, const void
     if ((rc = fill_zero(wb + wo.cu_busy, sizeof(uint64_t) * SB_CU_SLOTS, st)) != SB_OK) return rc;
     P.cu_busy = (unsigned long long*)(wb + wo.cu_busy);
   }
-  // key-major work: one workgroup per key tile, or per pair of key tiles of a selection block when blocks span several tiles
-  const int np = gb.r >= 2 ? 2 : 1;
-  const int64_t n_work = (int64_t)g.Hkv * (np == 2 ? key_tile_pairs(p, gb) : g.NQB);
-  if (n_work > 0x7fffffffll) { set_error("too many work items for one launch"); return SB_ERR_INVALID_ARG; }
   AttnParams Pq = P, Pk = P;
   Pq.work = (const int32_t*)(pb + po.work_fwd);
   Pk.work = (const int32_t*)(pb + po.work_bwd);
   if (g.D == 128) {
     rc = f32 ? launch_bwd<128, true>(g, Pq, st) : launch_bwd<128, false>(g, Pq, st);
     if (rc != SB_OK) return rc;
-    rc = f32 ? launch_dkv<128, true>(g, Pk, n_work, np, st) : launch_dkv<128, false>(g, Pk, n_work, np, st);
+    rc = f32 ? launch_dkv<128, true>(g, Pk, st) : launch_dkv<128, false>(g, Pk, st);
   } else {
     rc = f32 ? launch_bwd<64, true>(g, Pq, st) : launch_bwd<64, false>(g, Pq, st);
     if (rc != SB_OK) return rc;
-    rc = f32 ? launch_dkv<64, true>(g, Pk, n_work, np, st) : launch_dkv<64, false>(g, Pk, n_work, np, st);
+    rc = f32 ? launch_dkv<64, true>(g, Pk, st) : launch_dkv<64, false>(g, Pk, st);
   }
   return rc;
 }

@@ -131,16 +131,6 @@ Tables make_tables(const Geo& g, const sb_problem* p, void* base) {
   return r;
 }
 
-int64_t key_tile_pairs(const sb_problem* p, const Geo& gb) {
-  int64_t pairs = 0;
-  for (int s = 0; s < gb.S; ++s) {
-    const int64_t L = (int64_t)p->cu_seqlens_host[s + 1] - p->cu_seqlens_host[s];
-    const int64_t tiles = (L + 63) / 64, full = tiles / gb.r, rest = tiles % gb.r;
-    pairs += full * ((gb.r + 1) / 2) + (rest + 1) / 2;
-  }
-  return pairs;
-}
-
 PlanOffsets plan_offsets(const Geo& gb) {
   const Geo g = tile_geo(gb);  // the plan is laid out for the 64-row tiles the attention kernels work on
   PlanOffsets p{};

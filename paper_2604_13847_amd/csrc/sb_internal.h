@@ -107,7 +107,6 @@ struct PlanOffsets {
   size_t work_fwd;   // int32 [Hs*NQB]   row ids, longest first
   size_t colcost;    // int32 [Hkv*NQB]  tiles in each key-major column (summed over the group's heads)
   size_t work_bwd;   // int32 [Hkv*NQB]  column ids (g*NQB + qb): entry r*Hkv + g is the r-th heaviest column of KV head g
-                     // (selection blocks of several tiles: the r-th heaviest pair of key tiles, named by its first tile)
   size_t bitmap;     // uint32 [Hs * bm_words_unit] transpose bitmap: bit i of column (s,hs,j)
   size_t items;      // WorkItem [Hs*NQB]  descriptors of the query-major items, in work_fwd order
   // only for selection blocks larger than a tile (r > 1); everything above is then at tile level
@@ -131,9 +130,6 @@ struct WorkItem {
 };
 static_assert(sizeof(WorkItem) == 32, "WorkItem is loaded as 8 dwords");
 PlanOffsets plan_offsets(const Geo& g);
-// Selection blocks of r > 1 tiles: number of key-tile pairs (tiles 2a, 2a+1 of a block; the last tile of a ragged last
-// block may be alone) summed over the sequences.  The key-major work list then holds one entry per pair and KV head.
-int64_t key_tile_pairs(const sb_problem* p, const Geo& gb);
 
 struct WsOffsets {
   size_t cu_busy;    // uint64 [SB_CU_SLOTS]

@@ -103,30 +103,16 @@ __global__ __launch_bounds__(256) void plan_transpose_kernel(const int32_t* __re
 // at about the same time, while the heaviest-first rule still holds inside each list.
 // One workgroup per KV head: a counting sort on the column weight in LDS (histogram, suffix sums,
 // scatter); columns of equal weight end up in no particular order.
-// With selection blocks of r > 1 tiles the entries are pairs of key tiles (2a, 2a+1 of a block), named by their first
-// tile and weighted by the sum of the two columns; the second tile of a pair gets no entry of its own.
-__global__ __launch_bounds__(1024) void plan_bwd_order_kernel(const int32_t* __restrict__ colcost, int64_t NQB, int Hkv, int r,
-                                                              const int32_t* __restrict__ qb_off, const int32_t* __restrict__ qb_seq,
+__global__ __launch_bounds__(1024) void plan_bwd_order_kernel(const int32_t* __restrict__ colcost, int64_t NQB, int Hkv,
                                                               int32_t* __restrict__ work_bwd) {
   __shared__ int bins[kBwdBins];
   __shared__ int sh[1024];
   const int tid = threadIdx.x;
   const int64_t g = blockIdx.x;
   const int32_t* cost = colcost + g * NQB;
-  // weight of the entry that column c stands for, -1 if it has none
-  auto weight = [&](int64_t c) {
-    if (r == 1) return cost[c];
-    const int s = qb_seq[c];
-    const int it = (int)(c - qb_off[s]), n = qb_off[s + 1] - qb_off[s];
-    if ((it % r) & 1) return -1;
-    return cost[c] + (it + 1 < n ? cost[c + 1] : 0);
-  };
   for (int b = tid; b < kBwdBins; b += 1024) bins[b] = 0;
   __syncthreads();
-  for (int64_t c = tid; c < NQB; c += 1024) {
-    const int w = weight(c);
-    if (w >= 0) atomicAdd(&bins[min(w, kBwdBins - 1)], 1);
-  }
+  for (int64_t c = tid; c < NQB; c += 1024) atomicAdd(&bins[min(cost[c], kBwdBins - 1)], 1);
   __syncthreads();
   // bins[b] <- number of columns with a bin > b; thread t owns bins (kBwdBins-1 - t*per) downwards
   constexpr int per = kBwdBins / 1024;
@@ -146,9 +132,7 @@ __global__ __launch_bounds__(1024) void plan_bwd_order_kernel(const int32_t* __r
   for (int a = 0; a < per; ++a) { bins[kBwdBins - 1 - (tid * per + a)] = run; run += v[a]; }
   __syncthreads();
   for (int64_t c = tid; c < NQB; c += 1024) {
-    const int w = weight(c);
-    if (w < 0) continue;
-    const int rank = atomicAdd(&bins[min(w, kBwdBins - 1)], 1);
+    const int rank = atomicAdd(&bins[min(cost[c], kBwdBins - 1)], 1);
     work_bwd[(int64_t)rank * Hkv + g] = (int32_t)(g * NQB + c);
   }
 }
@@ -269,8 +253,7 @@ extern "C" int sb_plan_worklist(const sb_problem* p, const int32_t* sel_rowptr, 
   hipLaunchKernelGGL(plan_transpose_kernel, dim3((unsigned)words, (unsigned)g.Hs), dim3(256), 0, st, rowptr, idx, t.qb_off, t.bm_off,
                      g.S, g.NQB, g.Hs, g.G, g.mode, bitmap, colcost);
   SB_LAUNCH_CHECK("plan_transpose_kernel");
-  hipLaunchKernelGGL(plan_bwd_order_kernel, dim3((unsigned)g.Hkv), dim3(1024), 0, st, colcost, g.NQB, g.Hkv, gb.r, t.qb_off, t.qb_seq,
-                     work_bwd);
+  hipLaunchKernelGGL(plan_bwd_order_kernel, dim3((unsigned)g.Hkv), dim3(1024), 0, st, colcost, g.NQB, g.Hkv, work_bwd);
   SB_LAUNCH_CHECK("plan_bwd kernels");
   return SB_OK;
 }
