@@ -29,8 +29,9 @@
  *   - Selection CSR: row id = hs*NQB + qb_off[s] + i has c(s,i) = min(k_s, i+1) entries, the block
  *     indices (local to the sequence) kept by query block i, ascending, the last being i itself.
  *     sel_rowptr is therefore a closed form of cu_seqlens and topk.
- *   - Supported: block_size 64; head_dim 64 or 128; Hq % Hkv == 0; n_s <= SB_MAX_BLOCKS_PER_SEQ;
- *     in SB_SELECT_PER_KVGROUP Hq/Hkv <= 8.  Anything else returns SB_ERR_UNSUPPORTED.
+ *   - Supported: block_size 64, 128 or 256; head_dim 64 or 128; Hq % Hkv == 0; n_s <= SB_MAX_BLOCKS_PER_SEQ;
+ *     in SB_SELECT_PER_KVGROUP Hq/Hkv <= 8; selection entries and rows (at the granularity of 64-token tiles) must
+ *     fit 32-bit row pointers.  Anything else returns SB_ERR_UNSUPPORTED.
  *   - Degenerate inputs: empty sequences are allowed; T == 0 or S == 0 is a no-op returning SB_OK;
  *     k_s > n_s is clamped to n_s; k_s < 1 is an error.
  */
