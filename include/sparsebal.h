@@ -224,7 +224,8 @@ int sb_sab_batches(const sb_perf_table *perf, const int32_t *lengths, const doub
 #define SB_CU_SLOTS 512
 #define SB_INSTR_CU_BUSY 1
 #define SB_INSTR_KERNEL_EVENTS 2
-#define SB_NUM_KERNELS 9 /* pool, score, topk, plan, fwd, bwd_prep, bwd_dq, bwd_dkv, coverage */
+#define SB_NUM_KERNELS 9 /* pool, score, topk, plan, fwd, bwd_prep, bwd_dq, bwd_dkv, coverage; bwd_prep is the conversion of
+                            float32 inputs in the backward call (nothing for bf16 inputs) */
 int sb_set_instrumentation(int flag);
 int sb_read_cu_busy(const void *ws, uint64_t *busy_out_host, void *stream);
 int sb_read_kernel_times(double *total_ms_host, int64_t *launches_host);
