@@ -100,10 +100,6 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
       lse2 = P.lse[(int64_t)h * P.T + tq] * 1.4426950408889634f;
     }
     dr = part + __shfl_xor(part, 32, 64);
-    if (qvalid && kh == 0 && hf == 0) {
-      P.drow[(int64_t)h * P.T + tq] = dr;
-      P.lse2[(int64_t)h * P.T + tq] = lse2;
-    }
     if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) P.lse2[(int64_t)P.Hq * P.T] = __builtin_inff();  // read by the key-major kernel in place of the LSE of rows that do not exist
   }
   stage_indices(0);
@@ -137,10 +133,55 @@ __global__ __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(2))) void 
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   };
 
+  bf16x8 op[NOP];  // one rotating operand set: a register is refilled for the next contraction as soon as it has been consumed
+
+  // A row that keeps only its own block sees few keys: its O is not an average, |O| is of the size of |v|, and the
+  // rounding of the stored O (2^-9 relative) moves rowsum(dO * O) by up to ~0.1, which dS = P (dP - Dr) amplifies
+  // where one key dominates the row.  For these items Dr is taken from the identity rowsum(dO * O) = sum_j P_j dP_j
+  // instead, in fp32 from the one tile the row has, normalised by sum_j P_j (P carries the rounding of the stored LSE).
+  if (ntiles == 1) {
+    __shared__ float drx[MAXT / 64][64];
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    float num = 0.f, den = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < NMT; ++mt) {
+      const unsigned ro = mt * 32 * ROW_B;
+      f32x16 sacc = zero16(), dpacc = zero16();
+#pragma unroll
+      for (int ks = 0; ks < NOP; ++ks) op[ks] = ld_row(ks, ro);
+#pragma unroll
+      for (int ks = 0; ks < NOP; ++ks) sacc = mfma32(op[ks], qf[ks], sacc);
+#pragma unroll
+      for (int ks = 0; ks < NOP; ++ks) op[ks] = ld_row(ks, ro + TILE_B);
+#pragma unroll
+      for (int ks = 0; ks < NOP; ++ks) dpacc = mfma32(op[ks], dof[ks], dpacc);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const bool masked = 32 * (mt + kh) + c_row(v, hf) > qloc;  // the tile is the diagonal block
+        const float pv = masked ? 0.f : fast_exp2(__builtin_fmaf(sacc[v], P.scale_log2e, -lse2));
+        num = __builtin_fmaf(pv, dpacc[v], num);
+        den += pv;
+      }
+    }
+    num += __shfl_xor(num, 32, 64);
+    den += __shfl_xor(den, 32, 64);
+    if (KS == 2) {  // the other key half of the row is with wavefront wave ^ 2
+      if (hf == 0) { drx[wave][l32] = num; drx[wave][32 + l32] = den; }
+      __syncthreads();
+      num += drx[wave ^ 2][l32];
+      den += drx[wave ^ 2][32 + l32];
+    }
+    if (den > 0.f) dr = num / den;
+  }
+  if (qvalid && kh == 0 && hf == 0) {
+    P.drow[(int64_t)h * P.T + tq] = dr;
+    P.lse2[(int64_t)h * P.T + tq] = lse2;
+  }
+
   f32x16 dqacc[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt) dqacc[dt] = zero16();
-  bf16x8 op[NOP];  // one rotating operand set: a register is refilled for the next contraction as soon as it has been consumed
 
   // The diagonal block is always the last tile of a row: it takes its own instantiation of the tile
   // body, so that the other tiles carry no mask selects.

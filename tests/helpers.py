@@ -20,12 +20,26 @@ def to_host_f32(t: torch.Tensor) -> np.ndarray:
     return t.detach().float().cpu().numpy()
 
 
+_last_tensors = [None, None]
+
+
+def host_tensors(w: synth.Workload):
+    """w.tensors(), keeping the most recent workload's arrays: the full-size tests run one workload in several
+    selection modes, and drawing 2.7e9 normals takes longer than the GPU work."""
+    key = (w.seed, tuple(w.lens), w.Hq, w.Hkv, w.D, w.dtype)
+    if _last_tensors[0] != key:
+        _last_tensors[0], _last_tensors[1] = None, None      # free the previous workload before drawing the next
+        _last_tensors[1] = w.tensors()
+        _last_tensors[0] = key
+    return _last_tensors[1]
+
+
 class Run:
     """One workload pushed through sb_block_scores -> sb_select_topk -> sb_plan_worklist -> fwd -> bwd."""
 
     def __init__(self, w: synth.Workload, mode: int, topk=None, do_bwd=True, sel_override=None):
         self.w, self.mode = w, mode
-        t = w.tensors()
+        t = host_tensors(w)
         self.host = t                                   # float32 arrays holding the storage-type values
         if topk is None:
             topk = w.topk if w.topk is not None else sb.sb_keep_ratio_to_topk(w.cu, w.B, w.keep_ratio)
@@ -58,22 +72,35 @@ class Run:
         return tuple(synth.round_to_bf16(t[n]) for n in ("q", "k", "v", "do"))
 
 
-# Tolerance of the benchmark spec's metric: bf16 outputs against the float64 checker, max-abs 2e-2 and
-# mean-abs 2e-3.  The absolute bound is meant for values of order one: a bf16 output of magnitude
-# x carries a rounding error of up to |x| * 2^-9 on its own (0.016 at |x| = 8), so elements with
-# |ref| > 1 are held to the same bound relative to |ref|.
-MAX_ABS, MEAN_ABS = 2e-2, 2e-3
+# Tolerance of the benchmark spec's metric: bf16 outputs against the float64 checker, max-abs 2e-2 and mean-abs 2e-3.
+# An output stored as bf16 carries a rounding error of its own of up to half a unit in the last place, 2^-9 |x|
+# (0.016 at |x| = 8, and dV reaches 7-8 on dense rows), which the absolute bound cannot see; so every element is held to
+#     |got - ref| <= 2e-2 + 2^-8 |ref|
+# (the literal bound plus one bf16 unit in the last place of the reference), and the mean of |got - ref| to 2e-3.
+# check_close also returns the literal max-abs error, which the tests print.
+MAX_ABS, MEAN_ABS, ULP_BF16 = 2e-2, 2e-3, 2.0 ** -8
+# LSE is stored in float32; the forward's row sum adds the probabilities as rounded to bf16 (the weights it applies to
+# V), so it is off by at most 2^-9 relative, i.e. 2e-3 absolute in the logarithm; the rest is float32 arithmetic.
+LSE_ABS = 4e-3
 
 
 def err_stats(got: np.ndarray, ref: np.ndarray):
+    """(worst |err| / (2e-2 + 2^-8 |ref|), mean |err|, literal max |err|)"""
     d = np.abs(got.astype(np.float64) - ref)
     if not d.size:
-        return 0.0, 0.0
-    return float((d / np.maximum(1.0, np.abs(ref))).max()), float(d.mean())
+        return 0.0, 0.0, 0.0
+    return float((d / (MAX_ABS + ULP_BF16 * np.abs(ref))).max()), float(d.mean()), float(d.max())
 
 
 def check_close(name, got, ref):
-    mx, mn = err_stats(got, ref)
+    frac, mn, mx = err_stats(got, ref)
     assert np.isfinite(got).all(), f"{name}: non-finite values"
-    assert mx <= MAX_ABS and mn <= MEAN_ABS, f"{name}: max-err {mx:.4g} mean-abs {mn:.4g} (ref max {np.abs(ref).max():.3g})"
+    assert frac <= 1.0 and mn <= MEAN_ABS, (f"{name}: max-abs {mx:.4g} ({frac:.3f} of the bound 2e-2 + 2^-8|ref|) mean-abs {mn:.4g} "
+                                             f"(ref max {np.abs(ref).max():.3g})")
     return round(mx, 5), round(mn, 6)
+
+
+def check_lse(got, ref):
+    d = float(np.abs(np.asarray(got, dtype=np.float64) - ref).max()) if np.size(ref) else 0.0
+    assert d <= LSE_ABS, f"LSE: max-abs {d:.4g}"
+    return round(d, 6)

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import DEV, MAX_ABS, MEAN_ABS, Run, check_close, err_stats, to_host_f32
+from helpers import DEV, MEAN_ABS, Run, check_close, check_lse, err_stats, to_dev, to_host_f32
 from oracle import oracle as orc
 from paper_2604_13847_amd import binding as sb
 from paper_2604_13847_amd import synth
@@ -71,8 +71,7 @@ def check_attention(r: Run, bwd=True):
     q, k, v, do = r.oracle_inputs()
     O, LSE = orc.attn_fwd(r.opb, q, k, v, r.rowptr_h, r.idx_h, r.scale)
     stats = {"O": check_close("O", to_host_f32(r.o), O)}
-    lse = r.lse.cpu().numpy()
-    assert np.abs(lse - LSE).max() <= 1e-2, np.abs(lse - LSE).max()
+    stats["LSE"] = check_lse(r.lse.cpu().numpy(), LSE)
     if bwd:
         dQ, dK, dV = orc.attn_bwd(r.opb, q, k, v, do, r.rowptr_h, r.idx_h, r.scale)
         stats["dQ"] = check_close("dQ", to_host_f32(r.dq), dQ)
@@ -85,14 +84,66 @@ def full_check(w, mode, **kw):
     r = Run(w, mode, **kw)
     sc = check_scores(r)
     check_selection(r, sc)
-    check_plan(r)
+    if w.B == 64:          # (for larger selection blocks the plan is laid out for 64-token tiles)
+        check_plan(r)
     print(w, "mode", mode, check_attention(r), flush=True)
     return r
 
 
 def test_config1_fp32_inputs():
-    for seed in (0, 1):
-        full_check(synth.config1(seed), sb.SB_SELECT_PER_QHEAD)
+    for seed in (0, 1, 2):
+        r = full_check(synth.config1(seed), sb.SB_SELECT_PER_QHEAD)
+        # The kernels round float32 inputs to bf16 on entry and the check above gives the checker the same rounded values.
+        # Against the checker on the raw float32 values the input rounding shows as well (2^-9 relative on every
+        # operand of a 64-long dot product): reported, and held to twice the bound.
+        t = r.host
+        O, LSE = orc.attn_fwd(r.opb, t["q"], t["k"], t["v"], r.rowptr_h, r.idx_h, r.scale)
+        dQ, dK, dV = orc.attn_bwd(r.opb, t["q"], t["k"], t["v"], t["do"], r.rowptr_h, r.idx_h, r.scale)
+        for name, got, ref in (("O", r.o, O), ("dQ", r.dq, dQ), ("dK", r.dk, dK), ("dV", r.dv, dV)):
+            frac, mn, mx = err_stats(to_host_f32(got), ref)
+            print(f"seed {seed} {name} against the checker on the unrounded float32 inputs: max-abs {mx:.4g} mean-abs {mn:.4g}", flush=True)
+            assert frac <= 2.0 and mn <= 2 * MEAN_ABS
+
+
+def test_pooled_keys_against_block_means():
+    """kbar_out of sb_block_scores is the mean of K over the valid tokens of every block (tail blocks divide by their
+    own count)."""
+    for w in (synth.small_ragged(seed=41, lens=(200, 64, 1, 130, 0, 77, 450), Hq=4, Hkv=2, D=128, ratio=(0.3, 0.9)),
+              synth.small_ragged(seed=42, lens=(700, 257, 1), Hq=6, Hkv=3, D=64, B=256, ratio=(0.3, 0.9)),
+              synth.config1(0)):
+        t = w.tensors()
+        topk = w.topk if w.topk is not None else sb.sb_keep_ratio_to_topk(w.cu, w.B, w.keep_ratio)
+        pb = sb.Problem(w.cu, topk, w.Hq, w.Hkv, w.D, w.B, dtype=sb.SB_BF16 if w.dtype == "bf16" else sb.SB_F32, device=DEV)
+        _, kbar = sb.sb_block_scores(pb, to_dev(t["q"], w.dtype), to_dev(t["k"], w.dtype), want_kbar=True)
+        torch.cuda.synchronize()
+        po = orc.Problem(w.cu, w.Hq, w.Hkv, w.D, w.B, 0)
+        ref = orc.block_mean(po, t["k"])
+        got = kbar.cpu().numpy()[: ref.size].reshape(ref.shape)
+        assert np.abs(got - ref).max() <= 1e-6 * max(1.0, np.abs(ref).max()), np.abs(got - ref).max()
+
+
+# Workloads of a randomised sweep whose dQ / dK missed max-abs 2e-2 by a hair while Dr = rowsum(dO * O) was taken from the
+# stored bf16 O on rows with one or two visible keys (the second token of a sequence, or of a block that keeps only
+# itself).
+@pytest.mark.parametrize("case", [
+    dict(seed=1009, lens=[513, 1000, 786, 157], Hq=16, Hkv=2, D=128, B=256, ratio=(0.1, 0.3), mode=0),
+    dict(seed=1021, lens=[63, 65], Hq=12, Hkv=3, D=64, B=256, ratio=(1.0, 1.0), mode=1),
+    dict(seed=1019, lens=[1673, 1480, 65], Hq=8, Hkv=2, D=128, B=64, ratio=(0.0, 0.6), mode=0),
+])
+def test_rows_with_one_or_two_visible_keys_sweep_cases(case):
+    mode = case.pop("mode")
+    full_check(synth.small_ragged(**case), mode)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("D", [64, 128])
+def test_rows_that_keep_only_their_own_block(mode, D):
+    """Budget 1 everywhere and many very short sequences: every row sees at most its own block, the first rows of each
+    sequence one, two, three keys."""
+    lens = [2, 3, 1, 2, 65, 2, 130, 4, 2, 64, 2, 5] * 6
+    w = synth.small_ragged(seed=51 + D, lens=lens, Hq=8, Hkv=2, D=D, ratio=(0.0, 0.0))
+    r = full_check(w, mode)
+    assert np.all(r.topk == 1)
 
 
 @pytest.mark.parametrize("mode", [0, 1])
@@ -188,7 +239,7 @@ def test_selection_blocks_larger_than_a_tile(B, mode):
     dQ, dK, dV = orc.attn_bwd(r.opb, q, k, v, do, r.rowptr_h, r.idx_h, r.scale)
     for name, got, ref in (("O", r.o, O), ("dQ", r.dq, dQ), ("dK", r.dk, dK), ("dV", r.dv, dV)):
         print(name, check_close(name, to_host_f32(got), ref))
-    assert np.abs(r.lse.cpu().numpy() - LSE).max() <= 1e-2
+    print("LSE", check_lse(r.lse.cpu().numpy(), LSE))
 
 
 def test_block_256_full_budget_is_dense_causal():
@@ -207,14 +258,8 @@ def test_sixteen_query_heads_on_one_kv_head_per_qhead():
     q, k, v, do = r.oracle_inputs()
     O, LSE = orc.attn_fwd(r.opb, q, k, v, r.rowptr_h, r.idx_h, r.scale)
     dQ, dK, dV = orc.attn_bwd(r.opb, q, k, v, do, r.rowptr_h, r.idx_h, r.scale)
-    for name, got, ref in (("O", r.o, O), ("dQ", r.dq, dQ)):
+    for name, got, ref in (("O", r.o, O), ("dQ", r.dq, dQ), ("dK", r.dk, dK), ("dV", r.dv, dV)):
         print(name, check_close(name, to_host_f32(got), ref))
-    # dK and dV add up the bf16-rounded P and dS terms of 16 query heads instead of the benchmark's 4: their rounding
-    # noise grows with the square root of the number of terms, so the max bound is doubled here (the mean bound is not)
-    for name, got, ref in (("dK", r.dk, dK), ("dV", r.dv, dV)):
-        mx, mn = err_stats(to_host_f32(got), ref)
-        print(name, mx, mn)
-        assert mx <= 2 * MAX_ABS and mn <= MEAN_ABS
 
 
 @pytest.mark.parametrize("mode", [0, 1])
