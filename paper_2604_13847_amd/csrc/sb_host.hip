@@ -3,27 +3,50 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <atomic>
+#include <mutex>
+
 #include "sb_internal.h"
 
 namespace sb {
 
 static thread_local char g_err[512] = "";
-int g_instrument = 0;
+std::atomic<int> g_instrument{0};
 
+// Instrumentation state.  The flag and the event records are process-wide and guarded by one mutex, so calls from
+// several threads do not corrupt them (their records simply interleave).  Events are recycled through a free list:
+// after the first few steps a timed launch costs two hipEventRecord calls and no event creation.
 struct EventPair { hipEvent_t a, b; };
+static std::mutex g_ev_mu;
 static std::vector<EventPair> g_events[K_NUM];
+static std::vector<hipEvent_t> g_free_events;
+
+static hipEvent_t take_event() {
+  {
+    std::lock_guard<std::mutex> lock(g_ev_mu);
+    if (!g_free_events.empty()) {
+      hipEvent_t e = g_free_events.back();
+      g_free_events.pop_back();
+      return e;
+    }
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
 
 KernelTimer::KernelTimer(int slot_, hipStream_t st_) : slot(slot_), st(st_) {
   if (!(g_instrument & 2)) return;
-  hipEvent_t a;
-  if (hipEventCreate(&a) != hipSuccess) return;
+  hipEvent_t a = take_event();
+  if (!a) return;
   (void)hipEventRecord(a, st);
   start = (void*)a;
 }
 KernelTimer::~KernelTimer() {
   if (!start) return;
-  hipEvent_t b;
-  if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy((hipEvent_t)start); return; }
+  hipEvent_t b = take_event();
+  std::lock_guard<std::mutex> lock(g_ev_mu);
+  if (!b) { g_free_events.push_back((hipEvent_t)start); return; }
   (void)hipEventRecord(b, st);
   g_events[slot].push_back({(hipEvent_t)start, b});
 }
@@ -336,18 +359,27 @@ int sb_set_instrumentation(int flag) { g_instrument = flag & 3; return SB_OK; }
 
 int sb_read_kernel_times(double* total_ms, int64_t* launches) {
   if (!total_ms || !launches) { set_error("null argument"); return SB_ERR_INVALID_ARG; }
+  std::vector<EventPair> taken[K_NUM];
+  {
+    std::lock_guard<std::mutex> lock(g_ev_mu);
+    for (int k = 0; k < K_NUM; ++k) taken[k].swap(g_events[k]);
+  }
+  int rc = SB_OK;
   for (int k = 0; k < K_NUM; ++k) {
     total_ms[k] = 0.0; launches[k] = 0;
-    for (auto& e : g_events[k]) {
+    for (auto& e : taken[k]) {
       float ms = 0.f;
-      SB_CHECK_HIP(hipEventSynchronize(e.b));
-      SB_CHECK_HIP(hipEventElapsedTime(&ms, e.a, e.b));
+      if (rc == SB_OK && (hipEventSynchronize(e.b) != hipSuccess || hipEventElapsedTime(&ms, e.a, e.b) != hipSuccess)) {
+        set_error("reading a kernel's event pair failed");
+        rc = SB_ERR_HIP;
+      }
       total_ms[k] += ms; launches[k] += 1;
-      (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b);
     }
-    g_events[k].clear();
   }
-  return SB_OK;
+  std::lock_guard<std::mutex> lock(g_ev_mu);  // the events go back to the free list whether or not they could be read
+  for (int k = 0; k < K_NUM; ++k)
+    for (auto& e : taken[k]) { g_free_events.push_back(e.a); g_free_events.push_back(e.b); }
+  return rc;
 }
 
 int sb_read_cu_busy(const void* ws, uint64_t* out, void* stream) {

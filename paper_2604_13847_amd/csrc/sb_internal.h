@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <string>
 #include <vector>
 
@@ -76,6 +77,7 @@ inline __host__ __device__ int64_t tile_entries_before(int64_t it, int64_t k, in
 int make_geo(const sb_problem* p, Geo* g);
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+constexpr int kMaxDevices = 64;  // per-device state (attributes set, symbol addresses) is kept for this many ordinals
 
 // Device tables computed by geom_kernel from cu_seqlens_dev / topk_dev.
 struct TableOffsets {
@@ -147,7 +149,7 @@ size_t coverage_ws_bytes(const Geo& g);
 // into a HIP graph.
 int fill_zero(void* dst, size_t bytes, hipStream_t st);
 
-extern int g_instrument;  // bit 0: per-CU busy ticks, bit 1: HIP events around each kernel
+extern std::atomic<int> g_instrument;  // bit 0: per-CU busy ticks, bit 1: HIP events around each kernel
 
 // HIP-event bracket around one kernel launch on its own stream (only when bit 1 is set).
 enum KernelSlot { K_POOL = 0, K_SCORE, K_TOPK, K_PLAN, K_FWD, K_BWD_PREP, K_BWD_DQ, K_BWD_DKV, K_COVERAGE, K_NUM };

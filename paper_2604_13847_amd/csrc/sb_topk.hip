@@ -3,6 +3,8 @@
 // (score descending, block index ascending; -0 == +0; NaN below everything).
 // One wavefront per row: order-preserving 32-bit keys in LDS, a 4-pass radix select for the
 // threshold key, then an index-ordered compaction, so the result is a pure function of the scores.
+#include <mutex>
+
 #include "sb_internal.h"
 
 namespace sb {
@@ -135,12 +137,17 @@ static int select_launch(const Geo& g, const Tables& t, const float* scores, int
   int W = (int)(65536 / (sizeof(uint32_t) * (size_t)region_words));
   W = W < 1 ? 1 : (W > 4 ? 4 : W);
   const size_t smem = sizeof(uint32_t) * (size_t)region_words * W;
-  if (smem > 48 * 1024) {
-    static bool attr_set = false;
-    if (!attr_set) {
+  if (smem > 48 * 1024) {  // raise the kernel's dynamic LDS limit; once per device, whichever thread comes first
+    static std::mutex mu;
+    static bool attr_set[kMaxDevices] = {};
+    int dev = 0;
+    SB_CHECK_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) { set_error("device ordinal %d out of range", dev); return SB_ERR_UNSUPPORTED; }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!attr_set[dev]) {
       SB_CHECK_HIP(hipFuncSetAttribute((const void*)topk_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)(sizeof(uint32_t) * (SB_MAX_BLOCKS_PER_SEQ + 256))));
-      attr_set = true;
+      attr_set[dev] = true;
     }
   }
   const int64_t rows = (int64_t)g.Hs * g.NQB;

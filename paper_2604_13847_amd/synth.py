@@ -210,3 +210,28 @@ def small_ragged(seed=0, lens=(200, 64, 1, 130, 77), Hq=4, Hkv=2, D=64, B=64, ra
     """A small packed batch with ragged tails, several tiles per sequence; for element-wise parity."""
     return Workload("small", list(lens), Hq, Hkv, D, B=B,
                     keep_ratio=_ratios(seed, len(lens), ratio[0], ratio[1]), dtype=dtype, seed=seed)
+
+
+def sink_selection(cu, B, topk, Hs):
+    """A caller-supplied selection with the shape real attention maps have (an "attention sink" plus a local window):
+    query block i of a sequence with budget k keeps block 0, the diagonal block and the blocks right before it, c =
+    min(k, i + 1) blocks in all.  Every selection head gets the same rows.  Returns (rowptr [Hs*NQB+1], idx) in the CSR
+    layout of the library (rows ordered by selection head, then sequence, then query block; entries ascending).  Block 0
+    of a long sequence is then kept by every query block: the heaviest possible key-major column."""
+    cu = np.asarray(cu, dtype=np.int64)
+    rows_c, rows_i = [], []
+    for s in range(len(cu) - 1):
+        n = int((cu[s + 1] - cu[s] + B - 1) // B)
+        i = np.arange(n, dtype=np.int64)
+        rows_i.append(i)
+        rows_c.append(np.minimum(int(min(max(int(topk[s]), 1), max(n, 1))), i + 1))
+    c = np.concatenate(rows_c) if rows_c else np.zeros(0, dtype=np.int64)
+    i = np.concatenate(rows_i) if rows_i else np.zeros(0, dtype=np.int64)
+    start = np.concatenate([[0], np.cumsum(c)])
+    nnz = int(start[-1])
+    row_of = np.repeat(np.arange(len(c)), c)
+    pos = np.arange(nnz) - start[row_of]                       # position inside the row
+    ci, ii = c[row_of], i[row_of]
+    idx1 = np.where(pos == 0, np.where(ci == ii + 1, 0, np.where(ci == 1, ii, 0)), ii - (ci - 1) + pos)
+    rowptr = np.concatenate([(start[:-1][None, :] + nnz * np.arange(Hs)[:, None]).reshape(-1), [nnz * Hs]])
+    return rowptr.astype(np.int32), np.tile(idx1, Hs).astype(np.int32)
