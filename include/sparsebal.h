@@ -113,6 +113,17 @@ int sb_block_scores(const sb_problem *p, const void *q, const void *k, float *kb
 int sb_select_topk(const sb_problem *p, const float *scores, int32_t *sel_rowptr_out, int32_t *sel_idx_out,
                    void *ws, void *stream);
 
+/* sb_select_topk for callers that cannot allocate device memory or bring a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments minus `ws`, same results bit for bit.  The
+ * geometry tables that `ws` holds in sb_select_topk live in a device array built into the library (SB_STATIC_SELECT_WS_BYTES
+ * per GPU, held until the process ends); a problem whose tables (select_ws_bytes of sb_layout) do not fit returns
+ * SB_ERR_WORKSPACE_TOO_SMALL and enqueues nothing.  The call allocates and frees nothing.  All calls on one GPU share that
+ * array: calls on different streams of one GPU that overlap in time race; calls on one stream are ordered.  The first
+ * call on a device looks up the array's address (a host-side query, no allocation); make it outside graph capture. */
+#define SB_STATIC_SELECT_WS_BYTES (1 << 20)
+int sb_select_topk_static(const sb_problem *p, const float *scores, int32_t *sel_rowptr_out, int32_t *sel_idx_out,
+                          void *stream);
+
 /* sb_block_scores followed by sb_select_topk on the scores it wrote, in one call that computes the
  * sequence geometry once (paper section 2.2: the indexer and the Top-K selection are one step of the
  * method; the scores stay available in scores_out for the budget controller below).  Arguments as for

@@ -20,7 +20,7 @@ SB_BF16, SB_F32 = 0, 1
 SB_SELECT_PER_QHEAD, SB_SELECT_PER_KVGROUP = 0, 1
 SB_CU_SLOTS = 512
 
-EXPORTS = ["sb_get_layout", "sb_keep_ratio_to_topk", "sb_sel_rowptr_host", "sb_block_scores", "sb_select_topk", "sb_score_select",
+EXPORTS = ["sb_get_layout", "sb_keep_ratio_to_topk", "sb_sel_rowptr_host", "sb_block_scores", "sb_select_topk", "sb_select_topk_static", "sb_score_select",
            "sb_plan_worklist", "sb_sparse_attn_fwd", "sb_sparse_attn_bwd", "sb_score_coverage", "sb_perf_predict", "sb_perf_align", "sb_dst_tune",
            "sb_spar_update", "sb_spar_predict", "sb_balanced_partition", "sb_sab_batches",
            "sb_set_instrumentation", "sb_read_cu_busy", "sb_read_kernel_times",
@@ -146,6 +146,15 @@ def sb_select_topk(pb: Problem, scores, ws=None):
     idx = torch.empty(max(lay.sel_nnz, 1), dtype=torch.int32, device=scores.device)
     ws = ws if ws is not None else _bytes(lay.select_ws_bytes, scores.device)
     _check(lib().sb_select_topk(pb.ref(), _ptr(scores), _ptr(rowptr), _ptr(idx), _ptr(ws), _stream()))
+    return rowptr, idx
+
+
+def sb_select_topk_static(pb: Problem, scores, rowptr=None, idx=None):
+    """sb_select_topk without a workspace argument (the library's built-in scratch); outputs may be passed in."""
+    lay = pb.layout
+    rowptr = rowptr if rowptr is not None else torch.empty(lay.sel_rows + 1, dtype=torch.int32, device=scores.device)
+    idx = idx if idx is not None else torch.empty(max(lay.sel_nnz, 1), dtype=torch.int32, device=scores.device)
+    _check(lib().sb_select_topk_static(pb.ref(), _ptr(scores), _ptr(rowptr), _ptr(idx), _stream()))
     return rowptr, idx
 
 

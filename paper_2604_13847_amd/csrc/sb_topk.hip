@@ -190,3 +190,49 @@ extern "C" int sb_score_select(const sb_problem* p, const void* q, const void* k
   if (rc != SB_OK) return rc;
   return select_launch(g, make_tables(g, p, ws), scores_out, sel_rowptr_out, sel_idx_out, st);
 }
+
+// ---------------------------------------------------------------------------------------------
+// sb_select_topk for callers that cannot allocate: the geometry tables that `ws` holds in sb_select_topk live in a
+// file-scope device array instead.  In host code the array's name is only a stand-in; its device address is looked up
+// once per device (each GPU has its own copy at its own address) and that pointer is what the kernels receive.
+static __device__ __align__(256) unsigned char scratch[SB_STATIC_SELECT_WS_BYTES];
+
+static int static_scratch_ptr(void** out) {
+  static std::mutex mu;
+  static void* ptr_of_device[kMaxDevices] = {};
+  int dev = 0;
+  SB_CHECK_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) { set_error("device ordinal %d out of range", dev); return SB_ERR_UNSUPPORTED; }
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr_of_device[dev]) {
+    void* ptr = nullptr;
+    SB_CHECK_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) { set_error("hipGetSymbolAddress returned a null pointer"); return SB_ERR_HIP; }
+    ptr_of_device[dev] = ptr;
+  }
+  *out = ptr_of_device[dev];
+  return SB_OK;
+}
+
+extern "C" int sb_select_topk_static(const sb_problem* p, const float* scores, int32_t* sel_rowptr_out, int32_t* sel_idx_out,
+                                     void* stream) {
+  Geo g;
+  int rc = make_geo(p, &g);
+  if (rc != SB_OK) return rc;
+  if (!sel_rowptr_out) { set_error("null sel_rowptr_out"); return SB_ERR_INVALID_ARG; }
+  hipStream_t st = (hipStream_t)stream;
+  if (g.S == 0 || g.T == 0 || g.NQB == 0) return fill_zero(sel_rowptr_out, sizeof(int32_t), st);
+  if (!scores || !sel_idx_out) { set_error("null scores or sel_idx_out"); return SB_ERR_INVALID_ARG; }
+  const size_t need = align_up(table_offsets(g).bytes);
+  if (need > (size_t)SB_STATIC_SELECT_WS_BYTES) {
+    set_error("problem needs %zu bytes of geometry tables, the built-in scratch holds %d (use sb_select_topk)", need,
+              (int)SB_STATIC_SELECT_WS_BYTES);
+    return SB_ERR_WORKSPACE_TOO_SMALL;
+  }
+  void* ws = nullptr;
+  if ((rc = static_scratch_ptr(&ws)) != SB_OK) return rc;
+  // every table entry the selection reads is rewritten by the geometry kernel of this call: nothing has to start at zero
+  rc = launch_geom(g, p, ws, st);
+  if (rc != SB_OK) return rc;
+  return select_launch(g, make_tables(g, p, ws), scores, sel_rowptr_out, sel_idx_out, st);
+}
