@@ -134,10 +134,41 @@ int sb_score_select(const sb_problem *p, const void *q, const void *k, float *kb
 /* Work plan for the attention kernels: query-major work items (s,hs,i) ordered by decreasing
  * selected-block count (longest first, as in balanced partitioning by workload weight, paper
  * section 4.3), the key-major transpose of the selection (for every (s,hs,j) the set of query
- * blocks that kept j) and key-major items ordered by decreasing column weight.  plan_out: dev,
- * plan_bytes, opaque; it is valid for this problem and this selection only. */
+ * blocks that kept j) and key-major items ordered by decreasing weight; a column that very many query blocks
+ * kept (an attention sink) is cut into several items of bounded weight, so that no single workgroup becomes the
+ * straggler the paper's section 3.2 describes.  plan_out: dev, plan_bytes, opaque; it is valid for this problem and
+ * this selection only. */
 int sb_plan_worklist(const sb_problem *p, const int32_t *sel_rowptr, const int32_t *sel_idx, void *plan_out,
                      void *stream);
+
+/* Host only; for tests and tools that check the plan's properties (every item once, longest first, the transpose is a
+ * transpose).  Writes byte offsets into the plan buffer and three sizes to out[SB_PLAN_NUM_SECTIONS]:
+ *   QB_OFF   int32 [S+1]      first 64-token tile of every sequence
+ *   BM_OFF   int64 [S+1]      first bitmap word of every sequence (per selection head), n_s * ceil(n_s/32) words each
+ *   QB_SEQ   int32 [NQB]      sequence of every tile
+ *   WORK_FWD int32 [Hs*NQB]   selection rows (hs * NQB + tile) in launch order, longest first
+ *   COLCOST  int32 [Hkv*NQB]  (query block, query head) tiles of every key-major column g * NQB + tile
+ *   BITMAP   uint32           bit i of word (s, hs, j, i/32): query tile i of head hs kept key tile j
+ *   BWD_ITEMS 4 x int32 each  key-major items in launch order: column (or -1: none), bitmap words lo | hi << 16 the item
+ *                             covers, partial slot (or -1: the item is the whole column), tiles; BWD_ITEMS_COUNT entries
+ *   COUNTERS int32 [2]        partial slots in use, split columns
+ *   SPLIT_COLS 3 x int32 each column, first partial slot, parts
+ *   SPLIT_WEIGHT              a column with more tiles than this is cut into parts of at least this many
+ * (NQB counts 64-token tiles, whatever the selection block size.) */
+#define SB_PLAN_QB_OFF 0
+#define SB_PLAN_BM_OFF 1
+#define SB_PLAN_QB_SEQ 2
+#define SB_PLAN_WORK_FWD 3
+#define SB_PLAN_COLCOST 4
+#define SB_PLAN_BITMAP 5
+#define SB_PLAN_BWD_ITEMS 6
+#define SB_PLAN_COUNTERS 7
+#define SB_PLAN_SPLIT_COLS 8
+#define SB_PLAN_BWD_ITEMS_COUNT 9
+#define SB_PLAN_SPLIT_WEIGHT 10
+#define SB_PLAN_SPLIT_MAX 11
+#define SB_PLAN_NUM_SECTIONS 12
+int sb_plan_sections(const sb_problem *p, int64_t *out);
 
 /* Forward (Eq. 2): for every query row r of query block i and query head h,
  * O_r = sum_j softmax_j(softmax_scale * q_r.k_j) v_j over the keys j of the selected blocks that are

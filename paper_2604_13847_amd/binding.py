@@ -21,7 +21,7 @@ SB_SELECT_PER_QHEAD, SB_SELECT_PER_KVGROUP = 0, 1
 SB_CU_SLOTS = 512
 
 EXPORTS = ["sb_get_layout", "sb_keep_ratio_to_topk", "sb_sel_rowptr_host", "sb_block_scores", "sb_select_topk", "sb_select_topk_static", "sb_score_select",
-           "sb_plan_worklist", "sb_sparse_attn_fwd", "sb_sparse_attn_bwd", "sb_score_coverage", "sb_perf_predict", "sb_perf_align", "sb_dst_tune",
+           "sb_plan_worklist", "sb_plan_sections", "sb_sparse_attn_fwd", "sb_sparse_attn_bwd", "sb_score_coverage", "sb_perf_predict", "sb_perf_align", "sb_dst_tune",
            "sb_spar_update", "sb_spar_predict", "sb_balanced_partition", "sb_sab_batches",
            "sb_set_instrumentation", "sb_read_cu_busy", "sb_read_kernel_times",
            "sb_last_error", "sb_version"]
@@ -311,36 +311,31 @@ def sb_version() -> str:
 
 
 # ------------------------------------------------------------------ plan inspection (tests only)
+_PLAN_KEYS = ["qb_off", "bm_off", "qb_seq", "work_fwd", "colcost", "bitmap", "bwd_items", "counters", "split_cols",
+              "bwd_items_count", "split_weight", "split_max"]
+
+
 def plan_views(pb: Problem, plan: torch.Tensor):
-    """Decode the opaque plan for property tests; mirrors the layout order of the library."""
-    lay = pb.layout
-    S, NQB, Hs, Hkv = pb.S, lay.num_qblocks, lay.sel_heads, pb.Hkv
-
-    def up(x):
-        return (x + 255) // 256 * 256
-
-    o = 0
-    tab = {}
-    for name, size in (("qb_off", 4 * (S + 1)), ("sc_off", 8 * (S + 1)), ("row_base", 4 * (S + 1)), ("bm_off", 8 * (S + 1)),
-                       ("kclamp", 4 * (S + 1)), ("qb_seq", 4 * (NQB + 1))):
-        tab[name] = o
-        o = up(o + size)
-    tables_bytes = o
-    o = up(tables_bytes)
-    off = {}
-    for name, size in (("work_fwd", 4 * (Hs * NQB + 1)), ("colcost", 4 * (Hkv * NQB + 1)), ("work_bwd", 4 * (Hkv * NQB + 1))):
-        off[name] = o
-        o = up(o + size)
-    off["bitmap"] = o
+    """Decode the opaque plan for property tests, from the section offsets the library reports.  Everything is at the
+    granularity of 64-token tiles (NT of them), whatever the selection block size."""
+    sec = np.zeros(len(_PLAN_KEYS), dtype=np.int64)
+    _check(lib().sb_plan_sections(pb.ref(), _ptr(sec)))
+    o = dict(zip(_PLAN_KEYS, (int(x) for x in sec)))
+    S, Hkv = pb.S, pb.Hkv
     raw = plan.cpu().numpy()
 
     def view(start, count, dt):
         return raw[start:start + count * np.dtype(dt).itemsize].view(dt)
 
+    qb_off = view(o["qb_off"], S + 1, np.int32)
+    NT = int(qb_off[-1])
+    Hs = pb.layout.sel_heads
+    counters = view(o["counters"], 2, np.int32)
     return {
-        "qb_off": view(tab["qb_off"], S + 1, np.int32), "bm_off": view(tab["bm_off"], S + 1, np.int64),
-        "qb_seq": view(tab["qb_seq"], NQB, np.int32), "kclamp": view(tab["kclamp"], S, np.int32),
-        "work_fwd": view(off["work_fwd"], Hs * NQB, np.int32), "colcost": view(off["colcost"], Hkv * NQB, np.int32),
-        "work_bwd": view(off["work_bwd"], Hkv * NQB, np.int32),
-        "bitmap": raw[off["bitmap"]:].view(np.uint32),
+        "qb_off": qb_off, "bm_off": view(o["bm_off"], S + 1, np.int64), "qb_seq": view(o["qb_seq"], NT, np.int32),
+        "work_fwd": view(o["work_fwd"], Hs * NT, np.int32), "colcost": view(o["colcost"], Hkv * NT, np.int32),
+        "bitmap": raw[o["bitmap"]:o["bwd_items"]].view(np.uint32),
+        "bwd_items": view(o["bwd_items"], 4 * o["bwd_items_count"], np.int32).reshape(-1, 4),
+        "slots_used": int(counters[0]), "split_cols": view(o["split_cols"], 3 * int(counters[1]), np.int32).reshape(-1, 3),
+        "split_weight": o["split_weight"], "split_max": o["split_max"],
     }

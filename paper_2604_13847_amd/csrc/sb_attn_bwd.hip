@@ -340,11 +340,14 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
   __shared__ uint32_t bm_s[8][kCW];  // bitmap words of up to 8 selection heads
   __shared__ uint16_t tl_s[kCW * 32 * 8];  // the chunk's tiles in processing order
   __shared__ int ntl_s;
+  const ColItem item = P.bwd_items[blockIdx.x];
+  if (item.col < 0) return;  // the item lists are padded to their largest possible length
   BusyTimer timer;
   timer.start(P);
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-  const int64_t col = P.work[blockIdx.x];  // g * NQB + global block index
+  const int64_t col = item.col;  // g * NQB + global block index
+  const int wlo = item.wrange & 0xffff, whi = item.wrange >> 16;  // bitmap words of the column this item covers
   const int g = (int)(col / P.NQB);
   const int qbj = (int)(col - (int64_t)g * P.NQB);
   const int s = P.qb_seq[qbj];
@@ -465,8 +468,9 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
   int tt = 0;                                // tiles of the chunk processed so far: tile tt lives in buffer tt & 1
   for (int sel0 = 0; sel0 < nsel; sel0 += 8) {                  // selection heads in groups of 8
     const int ns8 = min(8, nsel - sel0);
-    for (int w0 = ((words - 1) & ~(kCW - 1)); w0 >= ((j >> 5) & ~(kCW - 1)); w0 -= kCW) {  // chunks of kCW bitmap words, last first
-      const int wn = min(kCW, words - w0);
+    for (int wend = whi, w0; wend > wlo; wend = w0) {  // chunks of up to kCW bitmap words, last first
+      w0 = max(wlo, wend - kCW);
+      const int wn = wend - w0;
       // ---- the chunk's tile list: entry = (query block - 32 w0) * 8 + head, ordered by query block, then head.
       // The list is walked backwards (last query block first): every column of a sequence then starts at
       // the same query block and, selecting at a similar density, stays close to its neighbours.
@@ -509,7 +513,7 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
       if (ntl == 0) continue;
       // the diagonal tiles (query block j itself) are the first of the list, i.e. the last to be processed: count them
       int nd = 0;
-      if (j >= 32 * w0 && j < 32 * (w0 + kCW)) {
+      if (j >= 32 * w0 && j < 32 * (w0 + wn)) {
         for (int sel = 0; sel < ns8; ++sel) nd += (int)((bm_s[sel][(j >> 5) - w0] >> (j & 31)) & 1u) * hpe;
         nd = __builtin_amdgcn_readfirstlane(nd);
       }
@@ -660,6 +664,19 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
 #undef SB_PIPE
 #undef SB_STAGE_FENCE
   // C layout: column = d (32dt + l32), register v = key row c_row(v, hf) of this wavefront's strip
+  if (item.slot >= 0) {  // a part of a split column: leave the fp32 partial sums for the reduction
+    float* part = P.partials + (size_t)item.slot * (2 * 64 * D);
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int kr = wave * 32 + c_row(v, hf);
+        part[kr * D + 32 * dt + l32] = dkacc[dt][v];
+        part[(64 + kr) * D + 32 * dt + l32] = dvacc[dt][v];
+      }
+    timer.stop(P);
+    return;
+  }
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
@@ -677,6 +694,39 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
       }
     }
   timer.stop(P);
+}
+
+// dK/dV of the split columns: the parts' fp32 partial sums added in part order (last query blocks first), then the
+// scale and the rounding of the unsplit path.  One workgroup per split column.
+template <int D, bool OUT_F32>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_reduce_kernel(AttnParams P) {
+  const int si = blockIdx.x;
+  if (si >= P.counters[1]) return;
+  const int64_t col = P.split_cols[3 * si];
+  const int slot0 = P.split_cols[3 * si + 1], np = P.split_cols[3 * si + 2];
+  const int g = (int)(col / P.NQB);
+  const int qbj = (int)(col - (int64_t)g * P.NQB);
+  const int s = P.qb_seq[qbj];
+  const int j = qbj - P.qb_off[s];
+  const int64_t seq0 = P.cu[s];
+  const int rows = min(64, P.cu[s + 1] - P.cu[s] - j * 64);
+  const float* part = P.partials + (size_t)slot0 * (2 * 64 * D);
+  for (int e = threadIdx.x; e < rows * D; e += 256) {
+    float dk = 0.f, dv = 0.f;
+    for (int p = 0; p < np; ++p) {
+      dk += part[(size_t)p * (2 * 64 * D) + e];
+      dv += part[(size_t)p * (2 * 64 * D) + 64 * D + e];
+    }
+    const int kr = e / D, d = e % D;
+    const int64_t off = ((seq0 + j * 64 + kr) * P.Hkv + g) * D + d;
+    if (OUT_F32) {
+      ((float*)P.dk)[off] = dk * P.scale;
+      ((float*)P.dv)[off] = dv;
+    } else {
+      ((bf16*)P.dk)[off] = (bf16)(dk * P.scale);
+      ((bf16*)P.dv)[off] = (bf16)dv;
+    }
+  }
 }
 
 int convert_f32_to_bf16(const void* src, void* dst, int64_t n, hipStream_t st);
@@ -699,10 +749,17 @@ static int launch_bwd(const Geo& g, const AttnParams& P, hipStream_t st) {
 
 template <int D, bool F32>
 static int launch_dkv(const Geo& g, const AttnParams& P, hipStream_t st) {
-  dim3 grid((unsigned)(g.Hkv * g.NQB)), block(128);
+  const int64_t extra = split_extra_max(g);
+  const int64_t n_items = (int64_t)g.Hkv * (g.NQB + extra);
+  if (n_items > 0x7fffffffll) { set_error("too many key-major items for one launch"); return SB_ERR_INVALID_ARG; }
+  dim3 grid((unsigned)n_items), block(128);
   KernelTimer kt(K_BWD_DKV, st);
   hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, F32>), grid, block, 0, st, P);
   SB_LAUNCH_CHECK("attn_bwd_dkv_kernel");
+  if (extra > 0) {  // at most `extra` columns are split; workgroups beyond the actual count return at once
+    hipLaunchKernelGGL((attn_bwd_dkv_reduce_kernel<D, F32>), dim3((unsigned)extra), dim3(256), 0, st, P);
+    SB_LAUNCH_CHECK("attn_bwd_dkv_reduce_kernel");
+  }
   return SB_OK;
 }
 
@@ -748,6 +805,10 @@ extern "C" int sb_sparse_attn_bwd(const sb_problem* p, const void* q, const void
   P.idx = gb.r == 1 ? sel_idx : (const int32_t*)(pb + po.t_idx);
   P.items = (const WorkItem*)(pb + po.items);
   P.bitmap = (const uint32_t*)(pb + po.bitmap);
+  P.bwd_items = (const ColItem*)(pb + po.bwd_items);
+  P.split_cols = (const int32_t*)(pb + po.split_cols);
+  P.counters = (const int32_t*)(pb + po.counters);
+  P.partials = (float*)(wb + wo.partials);
   P.cu = t.cu; P.qb_off = t.qb_off; P.qb_seq = t.qb_seq; P.bm_off = t.bm_off;
   P.NQB = g.NQB; P.T = g.T; P.Hq = g.Hq; P.Hkv = g.Hkv; P.G = g.G; P.Hs = g.Hs; P.mode = g.mode;
   P.scale = g.softmax_scale; P.scale_log2e = g.softmax_scale * 1.4426950408889634f;
@@ -759,7 +820,7 @@ extern "C" int sb_sparse_attn_bwd(const sb_problem* p, const void* q, const void
   }
   AttnParams Pq = P, Pk = P;
   Pq.work = (const int32_t*)(pb + po.work_fwd);
-  Pk.work = (const int32_t*)(pb + po.work_bwd);
+  Pk.work = nullptr;  // the key-major kernel reads bwd_items
   if (g.D == 128) {
     rc = f32 ? launch_bwd<128, true>(g, Pq, st) : launch_bwd<128, false>(g, Pq, st);
     if (rc != SB_OK) return rc;

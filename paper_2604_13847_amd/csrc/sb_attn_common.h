@@ -22,6 +22,10 @@ struct AttnParams {
   const int32_t* rowptr; const int32_t* idx; const int32_t* work;
   const WorkItem* items;  // descriptors of the query-major items, in work order
   const uint32_t* bitmap;
+  const ColItem* bwd_items;    // key-major items (whole columns or parts of heavy ones), see ColItem
+  const int32_t* split_cols;   // (column, first partial slot, parts) of the split columns; counters[1] of them
+  const int32_t* counters;
+  float* partials;             // [slot][dK, dV][64][D] fp32 partial sums of the parts of split columns
   const int32_t* cu; const int32_t* qb_off; const int32_t* qb_seq; const int64_t* bm_off;
   int64_t NQB;
   int T, Hq, Hkv, G, Hs, mode;

@@ -463,6 +463,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void a
         for (int v = 0; v < 16; ++v)
           if (32 * mt + c_row(v, hf) > qloc) sacc[v] = -__builtin_inff();
       }
+      // max3 below is inline asm, whose reads of the matrix instructions' results the compiler's hazard recogniser
+      // does not see: a vector instruction may read a register written by an 8-pass matrix instruction only 12 wait
+      // states after it.  (The masked tile goes through compiler-visible selects first.)  Without the wait a lane now
+      // and then took a stale value into its running maximum: harmless for the result's accuracy (the softmax does
+      // not depend on the reference point) but not bitwise repeatable.
+      if (!diag) asm volatile("s_nop 7\n\ts_nop 3" : "+v"(sacc));
       // online softmax with a lazy running maximum: the reference m follows the true maximum only when
       // that has grown by more than kLazy (in log2 units), so p stays below 2^kLazy and the accumulated
       // O is rescaled only then; O and the row sum carry the same factor, so the result is the same

@@ -161,7 +161,6 @@ PlanOffsets plan_offsets(const Geo& gb) {
   p.tables = o;   o = align_up(o + table_offsets(g).bytes);
   p.work_fwd = o; o = align_up(o + sizeof(int32_t) * (size_t)(g.Hs * g.NQB + 1));
   p.colcost = o;  o = align_up(o + sizeof(int32_t) * (size_t)(g.Hkv * g.NQB + 1));
-  p.work_bwd = o; o = align_up(o + sizeof(int32_t) * (size_t)(g.Hkv * g.NQB + 1));
   p.bitmap = o;   o = align_up(o + sizeof(uint32_t) * (size_t)(g.Hs * g.bm_words_unit + 1));
   p.items = o;    o = align_up(o + sizeof(WorkItem) * (size_t)(g.Hs * g.NQB + 1));
   p.blk_tables = p.t_rowptr = p.t_idx = o;
@@ -170,6 +169,10 @@ PlanOffsets plan_offsets(const Geo& gb) {
     p.t_rowptr = o;   o = align_up(o + sizeof(int32_t) * (size_t)(g.Hs * g.NQB + 1));
     p.t_idx = o;      o = align_up(o + sizeof(int32_t) * (size_t)(g.Hs * g.nnz_unit + 1));
   }
+  const size_t E = (size_t)split_extra_max(g);
+  p.bwd_items = o;  o = align_up(o + sizeof(ColItem) * ((size_t)g.Hkv * ((size_t)g.NQB + E) + 1));
+  p.counters = o;   o = align_up(o + sizeof(int32_t) * 4);
+  p.split_cols = o; o = align_up(o + sizeof(int32_t) * (3 * E + 1));
   p.bytes = o;
   return p;
 }
@@ -187,6 +190,7 @@ static WsOffsets ws_offsets(const Geo& g, bool bwd) {
   w.doc = o; o = align_up(o + (bwd ? qbytes : 0));
   w.drow = o; o = align_up(o + (bwd ? sizeof(float) * (size_t)g.T * g.Hq : 0));
   w.lse2 = o; o = align_up(o + (bwd ? sizeof(float) * ((size_t)g.T * g.Hq + 1) : 0));  // + one +inf sentinel
+  w.partials = o; o = align_up(o + (bwd ? sizeof(float) * 2 * (size_t)split_extra_max(tile_geo(g)) * 2 * 64 * g.D : 0));  // tile_geo is idempotent
   w.bytes = o;
   return w;
 }
@@ -276,18 +280,19 @@ int launch_geom(const Geo& g, const sb_problem* p, void* base, hipStream_t st) {
   return SB_OK;
 }
 
-__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* __restrict__ dst, size_t n) {
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = 0u;
+__global__ __launch_bounds__(256) void fill_words_kernel(uint32_t* __restrict__ dst, size_t n, uint32_t value) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = value;
 }
 
-int fill_zero(void* dst, size_t bytes, hipStream_t st) {
+int fill_words(void* dst, size_t bytes, uint32_t value, hipStream_t st) {
   const size_t n = bytes / 4;
   if (n == 0) return SB_OK;
   const size_t blocks = (n + 255) / 256;
-  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, st, (uint32_t*)dst, n);
-  SB_LAUNCH_CHECK("fill_zero_kernel");
+  hipLaunchKernelGGL(fill_words_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, st, (uint32_t*)dst, n, value);
+  SB_LAUNCH_CHECK("fill_words_kernel");
   return SB_OK;
 }
+int fill_zero(void* dst, size_t bytes, hipStream_t st) { return fill_words(dst, bytes, 0u, st); }
 
 }  // namespace sb
 
@@ -316,6 +321,29 @@ int sb_get_layout(const sb_problem* p, sb_layout* out) {
   out->bwd_ws_bytes = (int64_t)bwd_ws_offsets(g).bytes;
   out->attended_pairs_per_head_sum = g.pairs_unit * g.Hq;
   out->coverage_ws_bytes = (int64_t)coverage_ws_bytes(g);
+  return SB_OK;
+}
+
+int sb_plan_sections(const sb_problem* p, int64_t* out) {
+  if (!out) { set_error("null out"); return SB_ERR_INVALID_ARG; }
+  Geo gb;
+  int rc = make_geo(p, &gb);
+  if (rc != SB_OK) return rc;
+  const Geo g = tile_geo(gb);
+  const PlanOffsets po = plan_offsets(gb);
+  const TableOffsets to = table_offsets(g);
+  out[SB_PLAN_QB_OFF] = (int64_t)(po.tables + to.qb_off);
+  out[SB_PLAN_BM_OFF] = (int64_t)(po.tables + to.bm_off);
+  out[SB_PLAN_QB_SEQ] = (int64_t)(po.tables + to.qb_seq);
+  out[SB_PLAN_WORK_FWD] = (int64_t)po.work_fwd;
+  out[SB_PLAN_COLCOST] = (int64_t)po.colcost;
+  out[SB_PLAN_BITMAP] = (int64_t)po.bitmap;
+  out[SB_PLAN_BWD_ITEMS] = (int64_t)po.bwd_items;
+  out[SB_PLAN_COUNTERS] = (int64_t)po.counters;
+  out[SB_PLAN_SPLIT_COLS] = (int64_t)po.split_cols;
+  out[SB_PLAN_BWD_ITEMS_COUNT] = (int64_t)g.Hkv * (g.NQB + split_extra_max(g));
+  out[SB_PLAN_SPLIT_WEIGHT] = split_weight(g);
+  out[SB_PLAN_SPLIT_MAX] = split_extra_max(g);
   return SB_OK;
 }
 

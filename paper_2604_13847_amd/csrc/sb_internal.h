@@ -108,7 +108,9 @@ struct PlanOffsets {
   size_t tables;     // TableOffsets area
   size_t work_fwd;   // int32 [Hs*NQB]   row ids, longest first
   size_t colcost;    // int32 [Hkv*NQB]  tiles in each key-major column (summed over the group's heads)
-  size_t work_bwd;   // int32 [Hkv*NQB]  column ids (g*NQB + qb): entry r*Hkv + g is the r-th heaviest column of KV head g
+  size_t bwd_items;  // ColItem [Hkv*(NQB+E)]  key-major items: entry r*Hkv + g is the r-th heaviest item of KV head g (col = -1: none)
+  size_t counters;   // int32 [4]  {partial slots in use, split columns}, zeroed by every plan call
+  size_t split_cols; // int32 [3*E]  (column, first partial slot, parts) of every split column
   size_t bitmap;     // uint32 [Hs * bm_words_unit] transpose bitmap: bit i of column (s,hs,j)
   size_t items;      // WorkItem [Hs*NQB]  descriptors of the query-major items, in work_fwd order
   // only for selection blocks larger than a tile (r > 1); everything above is then at tile level
@@ -118,6 +120,22 @@ struct PlanOffsets {
   size_t bytes;
 };
 constexpr int kBwdBins = 4096;
+// A key-major column (s, g, j) is one work item unless it is heavier than split_weight() tiles: then it is cut, at the
+// granularity of 32 query blocks, into parts of at least that weight that are separate work items; the parts leave
+// fp32 partial dK/dV in the backward workspace and a reduction adds them in part order.  The bounds below follow from
+// "every part but a column's last has at least split_weight() tiles": at most split_extra_max() parts close, so there are
+// at most that many split columns, that many items more than columns (per KV head and overall), and twice that many
+// partial slots.  All three are functions of the problem's sizes alone, so the host can size buffers and grids.
+struct ColItem {
+  int32_t col;     // g * NQB + global block index of the key block, or -1
+  int32_t wrange;  // bitmap words [lo, hi) of the column this item covers: lo | hi << 16
+  int32_t slot;    // partial slot of this part, or -1: the item is the whole column and writes dK/dV itself
+  int32_t weight;  // (query block, query head) tiles of the item
+};
+static_assert(sizeof(ColItem) == 16, "ColItem is loaded as 4 dwords");
+inline int64_t bwd_total_tiles(const Geo& tg) { return (int64_t)tg.Hq * tg.nnz_unit; }  // tg = tile_geo(...)
+inline int split_weight(const Geo& tg) { const int64_t w = (bwd_total_tiles(tg) + 4095) / 4096; return (int)(w < 512 ? 512 : w); }
+inline int split_extra_max(const Geo& tg) { return (int)(bwd_total_tiles(tg) / split_weight(tg)); }
 // Everything a query-major workgroup needs to know about its item, so that it starts with one
 // 32-byte load instead of a chain of dependent table lookups.
 struct WorkItem {
@@ -138,6 +156,7 @@ struct WsOffsets {
   size_t qc, kc, vc, oc, doc;  // bf16 copies when dtype == SB_F32 (0 size otherwise)
   size_t drow;       // float [Hq][T]
   size_t lse2;       // float [Hq][T]
+  size_t partials;   // float [2*E][dK, dV][64][D]  partial sums of the parts of split key-major columns
   size_t bytes;
 };
 WsOffsets fwd_ws_offsets(const Geo& g);
@@ -148,6 +167,7 @@ size_t coverage_ws_bytes(const Geo& g);
 // Zero `bytes` (a multiple of 4) at `dst` with a small kernel on `st`: unlike a memset node this is safe to record
 // into a HIP graph.
 int fill_zero(void* dst, size_t bytes, hipStream_t st);
+int fill_words(void* dst, size_t bytes, uint32_t value, hipStream_t st);
 
 extern std::atomic<int> g_instrument;  // bit 0: per-CU busy ticks, bit 1: HIP events around each kernel
 

@@ -97,24 +97,72 @@ __global__ __launch_bounds__(256) void plan_transpose_kernel(const int32_t* __re
   }
 }
 
-// Key-major columns are ordered heaviest first separately for every KV head g, and the Hkv lists
-// are interleaved (position = rank_in_g * Hkv + g).  Neighbouring workgroups of one KV head then
-// walk neighbouring key blocks of one sequence and meet the same Q/dO tiles in the L2 of their XCD
-// at about the same time, while the heaviest-first rule still holds inside each list.
-// One workgroup per KV head: a counting sort on the column weight in LDS (histogram, suffix sums,
-// scatter); columns of equal weight end up in no particular order.
-__global__ __launch_bounds__(1024) void plan_bwd_order_kernel(const int32_t* __restrict__ colcost, int64_t NQB, int Hkv,
-                                                              int32_t* __restrict__ work_bwd) {
+// Key-major items are ordered heaviest first separately for every KV head g, and the Hkv lists are
+// interleaved (position = rank_in_g * Hkv + g).  Neighbouring workgroups of one KV head then walk
+// neighbouring key blocks of one sequence and meet the same Q/dO tiles in the L2 of their XCD at
+// about the same time, while the heaviest-first rule still holds inside each list.
+// An item is a whole column, or, for a column heavier than `wmax` tiles, one of its parts: the column's
+// bitmap words are walked from the last query block down (the order the backward kernel uses) and a part
+// closes as soon as it has gathered wmax tiles (see ColItem).  A column kept by every query block of a
+// long sequence (an attention sink) would otherwise be one workgroup's job for longer than the rest of
+// the launch takes.
+// One workgroup per KV head: a counting sort on the item weight in LDS (histogram, suffix sums,
+// scatter); items of equal weight end up in no particular order.
+struct ColumnWalk {
+  const uint32_t* bm;  // first bitmap word of the column's first selection head
+  int64_t head_stride; // words between the same column of consecutive selection heads
+  int nsel, hpe, words, wj;
+  __device__ inline int word_weight(int w) const {
+    int t = 0;
+    for (int sel = 0; sel < nsel; ++sel) t += __popc(bm[sel * head_stride + w]);
+    return t * hpe;
+  }
+  // calls emit(lo, hi, weight) for every part, last query blocks first; returns the number of parts
+  template <typename F>
+  __device__ inline int parts(int wmax, F emit) const {
+    int acc = 0, hi = words, np = 0;
+    for (int w = words - 1; w >= wj; --w) {
+      acc += word_weight(w);
+      if (acc >= wmax && w > wj) { emit(w, hi, acc); hi = w; acc = 0; ++np; }
+    }
+    emit(wj, hi, acc);
+    return np + 1;
+  }
+};
+
+__global__ __launch_bounds__(1024) void plan_bwd_order_kernel(const int32_t* __restrict__ colcost, const uint32_t* __restrict__ bitmap,
+                                                              const int32_t* __restrict__ qb_off, const int32_t* __restrict__ qb_seq,
+                                                              const int64_t* __restrict__ bm_off, int64_t NQB, int Hkv, int Hs, int G,
+                                                              int mode, int wmax, ColItem* __restrict__ items,
+                                                              int32_t* __restrict__ counters, int32_t* __restrict__ split_cols) {
   __shared__ int bins[kBwdBins];
   __shared__ int sh[1024];
   const int tid = threadIdx.x;
   const int64_t g = blockIdx.x;
   const int32_t* cost = colcost + g * NQB;
+  auto walk_of = [&](int64_t c) {
+    ColumnWalk cw;
+    const int s = qb_seq[c], j = (int)(c - qb_off[s]), n = qb_off[s + 1] - qb_off[s];
+    cw.words = (n + 31) >> 5;
+    cw.wj = j >> 5;
+    cw.nsel = mode == SB_SELECT_PER_QHEAD ? G : 1;
+    cw.hpe = mode == SB_SELECT_PER_QHEAD ? 1 : G;
+    const int64_t hs0 = mode == SB_SELECT_PER_QHEAD ? g * G : g;
+    cw.head_stride = (int64_t)n * cw.words;
+    cw.bm = bitmap + (int64_t)Hs * bm_off[s] + (hs0 * n + j) * cw.words;
+    return cw;
+  };
   for (int b = tid; b < kBwdBins; b += 1024) bins[b] = 0;
   __syncthreads();
-  for (int64_t c = tid; c < NQB; c += 1024) atomicAdd(&bins[min(cost[c], kBwdBins - 1)], 1);
+  for (int64_t c = tid; c < NQB; c += 1024) {
+    if (cost[c] <= wmax) {
+      atomicAdd(&bins[min(cost[c], kBwdBins - 1)], 1);
+    } else {
+      walk_of(c).parts(wmax, [&](int, int, int wt) { atomicAdd(&bins[min(wt, kBwdBins - 1)], 1); });
+    }
+  }
   __syncthreads();
-  // bins[b] <- number of columns with a bin > b; thread t owns bins (kBwdBins-1 - t*per) downwards
+  // bins[b] <- number of items with a bin > b; thread t owns bins (kBwdBins-1 - t*per) downwards
   constexpr int per = kBwdBins / 1024;
   int v[per], sum = 0;
 #pragma unroll
@@ -132,8 +180,24 @@ __global__ __launch_bounds__(1024) void plan_bwd_order_kernel(const int32_t* __r
   for (int a = 0; a < per; ++a) { bins[kBwdBins - 1 - (tid * per + a)] = run; run += v[a]; }
   __syncthreads();
   for (int64_t c = tid; c < NQB; c += 1024) {
-    const int rank = atomicAdd(&bins[min(cost[c], kBwdBins - 1)], 1);
-    work_bwd[(int64_t)rank * Hkv + g] = (int32_t)(g * NQB + c);
+    const int32_t col = (int32_t)(g * NQB + c);
+    const ColumnWalk cw = walk_of(c);
+    int np = 1;
+    if (cost[c] > wmax) np = cw.parts(wmax, [](int, int, int) {});
+    if (np == 1) {
+      const int rank = atomicAdd(&bins[min(cost[c], kBwdBins - 1)], 1);
+      items[(int64_t)rank * Hkv + g] = ColItem{col, cw.wj | (cw.words << 16), -1, cost[c]};
+    } else {
+      const int slot0 = atomicAdd(&counters[0], np);
+      const int si = atomicAdd(&counters[1], 1);
+      split_cols[3 * si] = col; split_cols[3 * si + 1] = slot0; split_cols[3 * si + 2] = np;
+      int part = 0;
+      cw.parts(wmax, [&](int lo, int hi, int wt) {
+        const int rank = atomicAdd(&bins[min(wt, kBwdBins - 1)], 1);
+        items[(int64_t)rank * Hkv + g] = ColItem{col, lo | (hi << 16), slot0 + part, wt};
+        ++part;
+      });
+    }
   }
 }
 
@@ -219,7 +283,8 @@ extern "C" int sb_plan_worklist(const sb_problem* p, const int32_t* sel_rowptr, 
   Tables t = make_tables(g, p, base + po.tables);
   int32_t* work_fwd = (int32_t*)(base + po.work_fwd);
   int32_t* colcost = (int32_t*)(base + po.colcost);
-  int32_t* work_bwd = (int32_t*)(base + po.work_bwd);
+  ColItem* bwd_items = (ColItem*)(base + po.bwd_items);
+  int32_t* counters = (int32_t*)(base + po.counters);
   uint32_t* bitmap = (uint32_t*)(base + po.bitmap);
   const int64_t rows = (int64_t)g.Hs * g.NQB, ncol = (int64_t)g.Hkv * g.NQB;
   KernelTimer kt(K_PLAN, st);
@@ -253,7 +318,12 @@ extern "C" int sb_plan_worklist(const sb_problem* p, const int32_t* sel_rowptr, 
   hipLaunchKernelGGL(plan_transpose_kernel, dim3((unsigned)words, (unsigned)g.Hs), dim3(256), 0, st, rowptr, idx, t.qb_off, t.bm_off,
                      g.S, g.NQB, g.Hs, g.G, g.mode, bitmap, colcost);
   SB_LAUNCH_CHECK("plan_transpose_kernel");
-  hipLaunchKernelGGL(plan_bwd_order_kernel, dim3((unsigned)g.Hkv), dim3(1024), 0, st, colcost, g.NQB, g.Hkv, work_bwd);
+  // the item lists are padded to their largest possible length; unused entries say "no item"
+  const size_t n_items = (size_t)g.Hkv * ((size_t)g.NQB + (size_t)split_extra_max(g));
+  if ((rc = fill_words(bwd_items, sizeof(ColItem) * n_items, 0xffffffffu, st)) != SB_OK) return rc;
+  if ((rc = fill_zero(counters, sizeof(int32_t) * 4, st)) != SB_OK) return rc;
+  hipLaunchKernelGGL(plan_bwd_order_kernel, dim3((unsigned)g.Hkv), dim3(1024), 0, st, colcost, bitmap, t.qb_off, t.qb_seq, t.bm_off,
+                     g.NQB, g.Hkv, g.Hs, g.G, g.mode, split_weight(g), bwd_items, counters, (int32_t*)(base + po.split_cols));
   SB_LAUNCH_CHECK("plan_bwd kernels");
   return SB_OK;
 }

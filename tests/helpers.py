@@ -104,3 +104,41 @@ def check_lse(got, ref):
     d = float(np.abs(np.asarray(got, dtype=np.float64) - ref).max()) if np.size(ref) else 0.0
     assert d <= LSE_ABS, f"LSE: max-abs {d:.4g}"
     return round(d, 6)
+
+
+def check_bwd_items(pv, colcost, nblk, qb_off, NQB, Hkv):
+    """Key-major items: per KV head heaviest first; every column covered exactly once by one item or by parts with
+    disjoint word ranges that span the column; only a column's last part may be lighter than the split weight."""
+    items = pv["bwd_items"]
+    wmax = pv["split_weight"]
+    seq_of = np.repeat(np.arange(len(nblk)), nblk)
+    parts = {}
+    for g in range(Hkv):
+        mine = items[g::Hkv]
+        valid = mine[:, 0] >= 0
+        nv = int(valid.sum())
+        assert valid[:nv].all() and not valid[nv:].any()                      # the padding is at the end
+        assert np.all(mine[:nv, 0] // NQB == g)
+        assert np.all(np.diff(np.minimum(mine[:nv, 3], 4095)) <= 0)           # heaviest first
+        for col, wr, slot, wt in mine[:nv]:
+            parts.setdefault(int(col), []).append((int(wr) & 0xffff, int(wr) >> 16, int(slot), int(wt)))
+    assert sorted(parts) == list(range(Hkv * NQB))                            # every column has an item
+    split = {int(c): (int(s0), int(n)) for c, s0, n in pv["split_cols"]}
+    slots = []
+    for col, ps in parts.items():
+        qb = col % NQB
+        s = seq_of[qb]
+        j, words = qb - int(qb_off[s]), (nblk[s] + 31) // 32
+        ps.sort(key=lambda x: -x[0])                                          # part 0 covers the last query blocks
+        assert ps[0][1] == words and ps[-1][0] == j // 32
+        assert all(a[0] == b[1] for a, b in zip(ps[:-1], ps[1:]))             # contiguous, disjoint
+        assert sum(x[3] for x in ps) == colcost[col]
+        if len(ps) == 1:
+            assert ps[0][2] == -1 and col not in split
+        else:
+            assert colcost[col] > wmax and all(x[3] >= wmax for x in ps[:-1])
+            assert split[col] == (ps[0][2], len(ps)) and [x[2] for x in ps] == list(range(ps[0][2], ps[0][2] + len(ps)))
+            slots += [x[2] for x in ps]
+    assert sorted(slots) == list(range(pv["slots_used"])) and len(split) == len(pv["split_cols"])
+    assert len(split) <= pv["split_max"] and len(slots) <= 2 * pv["split_max"]
+    return len(split)
