@@ -173,12 +173,17 @@ def test_sab_matches_the_checker_and_balances_the_length_mix():
     for step in range(3):
         kfin = rng.integers(1, 64, size=n)
         spar.update(lens, kfin)
-        for L, k in zip(lens, kfin):      # the library keeps the running value in float: mirror its rounding per sample
-            b = sab.length_bin(edges, L)
-            ema[b] = float(k) if not seen[b] else float(np.float32(0.8 * ema[b] + (1.0 - 0.8) * float(k)))
-            seen[b] = True
+        ema, seen = sab.spar_update(ema, seen, edges, 0.8, lens, kfin)       # the checker keeps its state in float64
+    # The library keeps the running value in float32 (one step is computed in double and rounded once): every update
+    # adds at most half an ulp of a value below 64, and earlier errors decay by 0.8 per update, so the two states differ
+    # by at most 2^-24 * 64 / (1 - 0.8) = 1.9e-5.
+    assert np.array_equal(spar.seen.astype(bool), seen)
+    assert np.abs(spar.ema.astype(np.float64) - ema).max() <= 2.0 ** -24 * 64 / 0.2
     kpred = np.array([spar.predict(int(L), 16.0) for L in lens])
-    assert np.array_equal(kpred, np.array([sab.spar_predict(ema, seen, edges, L, 16.0) for L in lens]))
+    kref = np.array([sab.spar_predict(ema, seen, edges, L, 16.0) for L in lens])
+    assert np.abs(kpred - kref).max() <= 2.0 ** -24 * 64 / 0.2
+    # the predictions are exactly the stored state of the bin
+    assert np.array_equal(kpred, np.array([sab.spar_predict(spar.ema.astype(np.float64), seen, edges, L, 16.0) for L in lens]))
     assert sb.SparsityPredictor(edges).predict(5000, 12.0) == 12.0
     # weights and the two-level partition, exact
     for rank in range(4):
