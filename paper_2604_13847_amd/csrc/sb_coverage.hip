@@ -61,15 +61,35 @@ __global__ __launch_bounds__(256) void coverage_rows_kernel(const float* __restr
       mx = fmaxf(mx, x);
     }
     mx = block_reduce_256(mx, tmp, true);
-    // bitonic sort, descending
-    for (int k2 = 2; k2 <= N; k2 <<= 1) {
-      for (int j2 = k2 >> 1; j2 > 0; j2 >>= 1) {
-        __syncthreads();
-        for (int t = tid; t < (N >> 1); t += 256) {
-          const int lo = ((t / j2) * 2 * j2) + (t % j2), hi = lo + j2;
-          const bool desc = (lo & k2) == 0;
-          const float a = keys[lo], b = keys[hi];
-          if (desc ? a < b : a > b) { keys[lo] = b; keys[hi] = a; }
+    // Bitonic sort, descending.  Pair p of a stage with compare distance j2 is (lo, lo + j2), lo = (p / j2) * 2 j2 + p % j2.
+    // The pairs are dealt to the four wavefronts in contiguous quarters: as long as j2 < N / 4 both elements of every
+    // pair of wavefront w lie in its own quarter of the keys, and so did the pairs that last wrote them, so the stage
+    // needs no workgroup barrier (the LDS operations of one wavefront complete in issue order); only the stages with
+    // j2 >= N / 4 (three of 66 for 2048 keys) exchange data between wavefronts.
+    {
+      const int wave = tid >> 6, lane = tid & 63;
+      const int ppw = N >> 3;  // pairs per wavefront (N >= 8 here: smaller rows take the plain loop)
+      bool shared_prev = true;  // the keys were written by all threads above
+      for (int k2 = 2; k2 <= N; k2 <<= 1) {
+        for (int j2 = k2 >> 1; j2 > 0; j2 >>= 1) {
+          const bool shared = N < 512 || j2 >= (N >> 2);
+          if (shared || shared_prev) __syncthreads(); else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          shared_prev = shared;
+          if (N < 512) {
+            for (int t = tid; t < (N >> 1); t += 256) {
+              const int lo = ((t & ~(j2 - 1)) << 1) | (t & (j2 - 1)), hi = lo + j2;  // j2 is a power of two
+              const bool desc = (lo & k2) == 0;
+              const float a = keys[lo], b = keys[hi];
+              if (desc ? a < b : a > b) { keys[lo] = b; keys[hi] = a; }
+            }
+          } else {
+            for (int t = wave * ppw + lane; t < (wave + 1) * ppw; t += 64) {
+              const int lo = ((t & ~(j2 - 1)) << 1) | (t & (j2 - 1)), hi = lo + j2;  // j2 is a power of two
+              const bool desc = (lo & k2) == 0;
+              const float a = keys[lo], b = keys[hi];
+              if (desc ? a < b : a > b) { keys[lo] = b; keys[hi] = a; }
+            }
+          }
         }
       }
     }
