@@ -207,6 +207,20 @@ def run(workload, mode_name, seed, steps, warmup, selection="topk", cu_busy=True
                       "frac_of_8TBps": round(b / (k_step[n] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4) if k_step[n] > 0 else None}
                   for n, b in hbm.items()}
 
+    # cold caches (outside the timed region): five more steps, each after 1 GiB of unrelated writes has gone through the
+    # L2 and the memory-side cache (256 MB); the figure above is the warm, steady-state one a training loop sees
+    flush = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+    cold = []
+    for _ in range(5):
+        flush.zero_()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(); step(); b.record()
+        torch.cuda.synchronize()
+        cold.append(a.elapsed_time(b))
+    del flush
+    res["cold_cache"] = {"ms_per_step_median": round(sorted(cold)[2], 4), "ms_per_step_min": round(min(cold), 4),
+                         "flush": "1 GiB written before every step"}
+
     if cu_busy:  # outside the timed region: one instrumented forward and one instrumented backward
         ncu = torch.cuda.get_device_properties(0).multi_processor_count
         spreads = {}
@@ -263,6 +277,7 @@ def main():
         "ms_per_step_median": r["ms_per_step_median"], "ms_per_step_min": r["ms_per_step_min"],
         "pct_of_bf16_mfma_peak": r["pct_of_bf16_mfma_peak"], "attention_only": r["attention_only"],
         "kernel_ms": r["kernel_ms"], "kernel_tflops": r["kernel_tflops"], "roofline": r["roofline"], "hbm": r["hbm"],
+        "cold_cache": r["cold_cache"],
     }
     for key in ("cu_busy", "cpu_baseline"):
         if key in r:
