@@ -29,6 +29,8 @@
  *   - Selection CSR: row id = hs*NQB + qb_off[s] + i has c(s,i) = min(k_s, i+1) entries, the block
  *     indices (local to the sequence) kept by query block i, ascending, the last being i itself.
  *     sel_rowptr is therefore a closed form of cu_seqlens and topk.
+ *   - No call takes the size of a buffer: every `ws`, `plan` and output must have at least the size sb_get_layout
+ *     reports for the same problem; an undersized buffer is overrun, not detected.
  *   - Supported: block_size 64, 128 or 256; head_dim 64 or 128; Hq % Hkv == 0; n_s <= SB_MAX_BLOCKS_PER_SEQ;
  *     in SB_SELECT_PER_KVGROUP Hq/Hkv <= 8; selection entries and rows (at the granularity of 64-token tiles) must
  *     fit 32-bit row pointers.  Anything else returns SB_ERR_UNSUPPORTED.
@@ -47,7 +49,7 @@ extern "C" {
 #define SB_OK 0
 #define SB_ERR_INVALID_ARG (-1)
 #define SB_ERR_UNSUPPORTED (-2)
-#define SB_ERR_WORKSPACE_TOO_SMALL (-3)
+#define SB_ERR_WORKSPACE_TOO_SMALL (-3) /* sb_select_topk_static: the problem's tables exceed the built-in scratch */
 #define SB_ERR_HIP (-4)
 
 #define SB_BF16 0 /* Q,K,V,O,dO,dQ,dK,dV are bfloat16 */
@@ -262,7 +264,10 @@ int sb_sab_batches(const sb_perf_table *perf, const int32_t *lengths, const doub
  *                     whose max/mean is the imbalance measure of the paper's Eq. 11 applied to CUs.
  *   SB_INSTR_KERNEL_EVENTS  every kernel launch is bracketed by HIP events on the launch stream;
  *                     sb_read_kernel_times waits for them, writes per-kernel total milliseconds and
- *                     launch counts (SB_NUM_KERNELS entries each, host) and resets the record. */
+ *                     launch counts (SB_NUM_KERNELS entries each, host) and resets the record.  The
+ *                     events are recycled: once a few steps have run, a timed launch creates none.
+ * The flag and the event record are process-wide (one mutex guards them): calls from several threads
+ * are safe, their records interleave.  bwd_dkv also covers the reduction of split key-major columns. */
 #define SB_CU_SLOTS 512
 #define SB_INSTR_CU_BUSY 1
 #define SB_INSTR_KERNEL_EVENTS 2
