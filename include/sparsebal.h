@@ -126,10 +126,16 @@ int sb_select_topk(const sb_problem *p, const float *scores, int32_t *sel_rowptr
 int sb_select_topk_static(const sb_problem *p, const float *scores, int32_t *sel_rowptr_out, int32_t *sel_idx_out,
                           void *stream);
 
-/* sb_block_scores followed by sb_select_topk on the scores it wrote, in one call that computes the
- * sequence geometry once (paper section 2.2: the indexer and the Top-K selection are one step of the
- * method; the scores stay available in scores_out for the budget controller below).  Arguments as for
- * the two calls; ws: dev, scores_ws_bytes.  Results are identical to calling the two separately. */
+/* The indexer and the Top-K selection as one step (paper section 2.2).  Arguments as for
+ * sb_block_scores and sb_select_topk; ws: dev, scores_ws_bytes.  sel_rowptr_out and sel_idx_out are
+ * bit-identical to calling the two separately, whichever form is used:
+ *   scores_out != NULL  the score matrix is written as by sb_block_scores (it stays available for the
+ *                       budget controller below) and the selection is taken from it;
+ *   scores_out == NULL  one kernel computes each row's scores on chip and selects there: the score
+ *                       matrix (scores_elems floats) is neither allocated nor written nor read back.
+ *                       A sequence so long that a single row of keys does not fit the compute unit's
+ *                       local memory returns SB_ERR_UNSUPPORTED (not reachable below
+ *                       SB_MAX_BLOCKS_PER_SEQ on gfx950). */
 int sb_score_select(const sb_problem *p, const void *q, const void *k, float *kbar_out, float *scores_out,
                     int32_t *sel_rowptr_out, int32_t *sel_idx_out, void *ws, void *stream);
 
@@ -271,8 +277,9 @@ int sb_sab_batches(const sb_perf_table *perf, const int32_t *lengths, const doub
 #define SB_CU_SLOTS 512
 #define SB_INSTR_CU_BUSY 1
 #define SB_INSTR_KERNEL_EVENTS 2
-#define SB_NUM_KERNELS 9 /* pool, score, topk, plan, fwd, bwd_prep, bwd_dq, bwd_dkv, coverage; bwd_prep is the conversion of
-                            float32 inputs in the backward call (nothing for bf16 inputs) */
+#define SB_NUM_KERNELS 10 /* pool, score, topk, plan, fwd, bwd_prep, bwd_dq, bwd_dkv, coverage, score_select; bwd_prep is the
+                             conversion of float32 inputs in the backward call (nothing for bf16 inputs); score_select is the
+                             single kernel of sb_score_select without scores_out */
 int sb_set_instrumentation(int flag);
 int sb_read_cu_busy(const void *ws, uint64_t *busy_out_host, void *stream);
 int sb_read_kernel_times(double *total_ms_host, int64_t *launches_host);

@@ -158,10 +158,11 @@ def sb_select_topk_static(pb: Problem, scores, rowptr=None, idx=None):
     return rowptr, idx
 
 
-def sb_score_select(pb: Problem, q, k, ws=None):
-    """Scores and selection in one call; returns (scores, sel_rowptr, sel_idx)."""
+def sb_score_select(pb: Problem, q, k, ws=None, want_scores=True):
+    """Scores and selection in one call; returns (scores, sel_rowptr, sel_idx); scores is None with want_scores=False
+    (the single-kernel form that keeps the scores on chip)."""
     lay = pb.layout
-    scores = torch.empty(max(lay.scores_elems, 1), dtype=torch.float32, device=q.device)
+    scores = torch.empty(max(lay.scores_elems, 1), dtype=torch.float32, device=q.device) if want_scores else None
     rowptr = torch.empty(lay.sel_rows + 1, dtype=torch.int32, device=q.device)
     idx = torch.empty(max(lay.sel_nnz, 1), dtype=torch.int32, device=q.device)
     ws = ws if ws is not None else _bytes(lay.scores_ws_bytes, q.device)
@@ -285,7 +286,7 @@ def sb_sab_batches(tab: PerfTable, lengths, k_pred, dp_size, dp_rank, num_microb
 
 
 SB_INSTR_CU_BUSY, SB_INSTR_KERNEL_EVENTS = 1, 2
-KERNEL_NAMES = ["pool", "score", "topk", "plan", "fwd", "bwd_prep", "bwd_dq", "bwd_dkv", "coverage"]
+KERNEL_NAMES = ["pool", "score", "topk", "plan", "fwd", "bwd_prep", "bwd_dq", "bwd_dkv", "coverage", "score_select"]
 
 
 def sb_set_instrumentation(flag: int):

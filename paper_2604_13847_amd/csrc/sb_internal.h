@@ -172,7 +172,7 @@ int fill_words(void* dst, size_t bytes, uint32_t value, hipStream_t st);
 extern std::atomic<int> g_instrument;  // bit 0: per-CU busy ticks, bit 1: HIP events around each kernel
 
 // HIP-event bracket around one kernel launch on its own stream (only when bit 1 is set).
-enum KernelSlot { K_POOL = 0, K_SCORE, K_TOPK, K_PLAN, K_FWD, K_BWD_PREP, K_BWD_DQ, K_BWD_DKV, K_COVERAGE, K_NUM };
+enum KernelSlot { K_POOL = 0, K_SCORE, K_TOPK, K_PLAN, K_FWD, K_BWD_PREP, K_BWD_DQ, K_BWD_DKV, K_COVERAGE, K_SCORE_SELECT, K_NUM };
 static_assert(K_NUM == SB_NUM_KERNELS, "kernel slots");
 struct KernelTimer {
   int slot; hipStream_t st; void* start = nullptr;

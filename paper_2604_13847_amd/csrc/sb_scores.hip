@@ -3,6 +3,7 @@
 // Pooling is HBM-bound (K and Q are read once); the score tiles run on the fp32 matrix cores and
 // write the score matrix once.
 #include "sb_internal.h"
+#include "sb_score_tile.h"
 
 namespace sb {
 
@@ -43,16 +44,15 @@ __global__ __launch_bounds__(256) void pool_kernel(const void* __restrict__ X, i
   *(float4*)(out + (int64_t)qb * cols + c0) = make_float4(a0 * inv, a1 * inv, a2 * inv, a3 * inv);
 }
 
-// Score tiles on the fp32 matrix cores (v_mfma_f32_32x32x2_f32: the selection is taken on fp32
-// scores, so the operands stay fp32).  One workgroup per (64 query blocks of one sequence, chunk of
-// up to kScChunk * 64 key blocks, selection head): the pooled query tile is staged in LDS once, the
-// pooled key tiles one after the other; each of the four wavefronts computes a 32 x 32 quarter of
-// every 64 x 64 score tile.  Tiles right of the diagonal are -infinity without being computed, and
-// the last chunk of a row tile also fills every column to its right with -infinity, so that the
-// whole n x n matrix is defined.  Splitting the columns over workgroups keeps the longest workgroup
-// short however long the sequence is.
+// Score tiles on the fp32 matrix cores (the selection is taken on fp32 scores, so the operands stay
+// fp32).  One workgroup per (64 query blocks of one sequence, chunk of up to kScChunk * 64 key
+// blocks, selection head): the pooled query tile is staged in LDS once, the pooled key tiles one
+// after the other; each of the four wavefronts keeps 16 query rows in registers and computes the
+// four 16 x 16 tiles of its rows in every 64 x 64 score tile.  Tiles right of the diagonal are
+// -infinity without being computed, and the last chunk of a row tile also fills every column to
+// its right with -infinity, so that the whole n x n matrix is defined.  Splitting the columns over
+// workgroups keeps the longest workgroup short however long the sequence is.
 constexpr int kScChunk = 4;
-typedef float f32x16s __attribute__((ext_vector_type(16)));
 
 // workgroups of a sequence with nt row tiles: sum over it < nt of (it / kScChunk + 1)
 __host__ __device__ inline int64_t score_items(int64_t nt) {
@@ -109,9 +109,10 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ qb
       }
     *(float4*)(qs + r * LD + c) = acc;
   }
-  const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-  const int wr = wave & 1, wc = wave >> 1;  // quarter of the 64 x 64 tile this wavefront computes
+  const int wave = tid >> 6, lane = tid & 63, l16 = lane & 15, kq = lane >> 4;
   const float ninf = -__builtin_inff();
+  float a[D / 4];  // this lane's quarter of query row 16 * wave + l16 (filled once the tile is staged)
+  bool have_a = false;
   for (int c = 0; c < kScChunk; ++c) {
     const int jt = jc * kScChunk + c, j0 = jt * 64;
     if (j0 >= n) break;
@@ -123,6 +124,10 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ qb
       continue;
     }
     __syncthreads();  // the previous key tile has been consumed (and, the first time, the query tile is staged)
+    if (!have_a) {
+      load_quarter<D>(a, qs + (16 * wave + l16) * LD, kq);
+      have_a = true;
+    }
     const int colsv = min(64, n - j0);
     for (int u = tid; u < 64 * (D / 4); u += 256) {
       const int r = u / (D / 4), cc = (u % (D / 4)) * 4;
@@ -131,28 +136,22 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ qb
       *(float4*)(ks + r * LD + cc) = v;
     }
     __syncthreads();
-    // A = pooled queries (row = lane % 32), B = pooled keys transposed (column = lane % 32); the lane half
-    // picks which of the two contraction slots of an instruction it feeds: slot (step 4t + e, half) is d = 8t + 4 half + e
-    f32x16s acc;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-    const float* qa = qs + (32 * wr + l32) * LD + 4 * hf;
-    const float* kb = ks + (32 * wc + l32) * LD + 4 * hf;
-#pragma unroll 4
-    for (int t = 0; t < D / 8; ++t) {
-      const float4 a = *(const float4*)(qa + 8 * t), b = *(const float4*)(kb + 8 * t);
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
-    }
-    // C layout: column = lane % 32, register v = row 8 (v / 4) + 4 half + v % 4
-    const int j = j0 + 32 * wc + l32;
-    if (j < n) {
+    for (int c4 = 0; c4 < 4; ++c4) {
+      const int j = j0 + 16 * c4 + l16;
+      const bool future = j0 + 16 * c4 > i0 + 16 * wave + 15;  // the whole 16 x 16 tile lies right of the diagonal
+      f32x4s acc = {0.f, 0.f, 0.f, 0.f};
+      if (!future) {
+        float b[D / 4];
+        load_quarter<D>(b, ks + (16 * c4 + l16) * LD, kq);
+        acc = score_tile16<D>(a, b);
+      }
+      if (j < n) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int i = i0 + 32 * wr + 8 * (v >> 2) + 4 * hf + (v & 3);
-        if (i < n) out[(int64_t)i * n + j] = j < i ? scale * acc[v] : ninf;
+        for (int v = 0; v < 4; ++v) {
+          const int i = i0 + 16 * wave + 4 * kq + v;
+          if (i < n) out[(int64_t)i * n + j] = j < i ? scale * acc[v] : ninf;
+        }
       }
     }
   }
@@ -161,6 +160,33 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ qb
     for (int r = 0; r < rows; ++r)
       for (int j = jstart + tid; j < n; j += 256) out[(int64_t)(i0 + r) * n + j] = ninf;
   }
+}
+
+// Mean-pools Q and K into the workspace behind the geometry tables.
+int launch_pool(const Geo& g, const sb_problem* p, const Tables& t, const void* q, const void* k, float* kbar_out, void* ws,
+                hipStream_t st, float** qbar_p, float** kbar_p) {
+  (void)p;
+  char* b = (char*)ws + align_up(table_offsets(g).bytes);
+  float* qbar = (float*)b;
+  float* kbar = (float*)(b + align_up(sizeof(float) * (size_t)g.NQB * g.Hq * g.D));
+  const int qcols = g.Hq * g.D, kcols = g.Hkv * g.D;
+  dim3 gq((unsigned)g.NQB, (unsigned)((qcols + 1023) / 1024)), gk((unsigned)g.NQB, (unsigned)((kcols + 1023) / 1024));
+  {
+    KernelTimer kt(K_POOL, st);
+    if (g.dtype == SB_F32) {
+      hipLaunchKernelGGL(pool_kernel<true>, gq, dim3(256), 0, st, q, qcols, t.cu, t.qb_off, t.qb_seq, g.B, qbar);
+      hipLaunchKernelGGL(pool_kernel<true>, gk, dim3(256), 0, st, k, kcols, t.cu, t.qb_off, t.qb_seq, g.B, kbar);
+    } else {
+      hipLaunchKernelGGL(pool_kernel<false>, gq, dim3(256), 0, st, q, qcols, t.cu, t.qb_off, t.qb_seq, g.B, qbar);
+      hipLaunchKernelGGL(pool_kernel<false>, gk, dim3(256), 0, st, k, kcols, t.cu, t.qb_off, t.qb_seq, g.B, kbar);
+    }
+  }
+  SB_LAUNCH_CHECK("pool_kernel");
+  if (kbar_out)
+    SB_CHECK_HIP(hipMemcpyAsync(kbar_out, kbar, sizeof(float) * (size_t)g.NQB * g.Hkv * g.D, hipMemcpyDeviceToDevice, st));
+  *qbar_p = qbar;
+  *kbar_p = kbar;
+  return SB_OK;
 }
 
 }  // namespace sb
@@ -178,24 +204,8 @@ extern "C" int sb_block_scores(const sb_problem* p, const void* q, const void* k
   rc = launch_geom(g, p, ws, st);
   if (rc != SB_OK) return rc;
   Tables t = make_tables(g, p, ws);
-  char* b = (char*)ws + align_up(table_offsets(g).bytes);
-  float* qbar = (float*)b;
-  float* kbar = (float*)(b + align_up(sizeof(float) * (size_t)g.NQB * g.Hq * g.D));
-  const int qcols = g.Hq * g.D, kcols = g.Hkv * g.D;
-  dim3 gq((unsigned)g.NQB, (unsigned)((qcols + 1023) / 1024)), gk((unsigned)g.NQB, (unsigned)((kcols + 1023) / 1024));
-  {
-  KernelTimer kt(K_POOL, st);
-  if (g.dtype == SB_F32) {
-    hipLaunchKernelGGL(pool_kernel<true>, gq, dim3(256), 0, st, q, qcols, t.cu, t.qb_off, t.qb_seq, g.B, qbar);
-    hipLaunchKernelGGL(pool_kernel<true>, gk, dim3(256), 0, st, k, kcols, t.cu, t.qb_off, t.qb_seq, g.B, kbar);
-  } else {
-    hipLaunchKernelGGL(pool_kernel<false>, gq, dim3(256), 0, st, q, qcols, t.cu, t.qb_off, t.qb_seq, g.B, qbar);
-    hipLaunchKernelGGL(pool_kernel<false>, gk, dim3(256), 0, st, k, kcols, t.cu, t.qb_off, t.qb_seq, g.B, kbar);
-  }
-  }
-  SB_LAUNCH_CHECK("pool_kernel");
-  if (kbar_out)
-    SB_CHECK_HIP(hipMemcpyAsync(kbar_out, kbar, sizeof(float) * (size_t)g.NQB * g.Hkv * g.D, hipMemcpyDeviceToDevice, st));
+  float *qbar = nullptr, *kbar = nullptr;
+  if ((rc = launch_pool(g, p, t, q, k, kbar_out, ws, st, &qbar, &kbar)) != SB_OK) return rc;
   int64_t items = 0;  // (sequence, row tile, column chunk) triples
   for (int s = 0; s < g.S; ++s) {
     const int64_t L = (int64_t)p->cu_seqlens_host[s + 1] - p->cu_seqlens_host[s];

@@ -6,19 +6,9 @@
 #include <mutex>
 
 #include "sb_internal.h"
+#include "sb_score_tile.h"
 
 namespace sb {
-
-__device__ inline uint32_t order_key(float x) {
-  if (x != x) return 0u;              // NaN: lowest
-  if (x == 0.0f) x = 0.0f;            // -0 and +0 share one key
-  uint32_t b = __float_as_uint(x);
-  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-}
-
-// LDS operations of one wavefront are carried out in issue order, so a wavefront that works alone
-// on its own LDS region needs no barrier between phases: only the compiler has to keep the order.
-__device__ inline void wave_lds_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 // One wavefront per row (several rows per workgroup, no workgroup barrier anywhere): keys and a
 // 256-bin histogram in the wavefront's own LDS region.
@@ -40,10 +30,7 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ sco
   const int n = qb_off[s + 1] - qb_off[s];
   const int k = kclamp[s];
   const int c = min(k, i + 1);
-  // closed-form row start: head offset + sequence offset + rows before i in this sequence
-  const int m0 = min(i, k);  // rows i' < i with i'+1 <= k contribute i'+1, the rest contribute k
-  const int64_t before = (int64_t)m0 * (m0 + 1) / 2 + (int64_t)(i - m0) * k;
-  const int64_t start = (int64_t)hs * nnz_unit + row_base[s] + before;
+  const int64_t start = (int64_t)hs * nnz_unit + row_base[s] + sel_rows_before(i, k);
   if (lane == 0) {
     rowptr[row_id] = (int32_t)start;
     if (row_id == (int64_t)Hs * NQB - 1) rowptr[(int64_t)Hs * NQB] = (int32_t)(start + c);
@@ -67,61 +54,85 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ sco
     for (int u = 0; u < 8; ++u)
       if (j0 + 64 * u < m) keys[j0 + 64 * u] = order_key(x[u]);
   }
-  // radix select, 8 bits per pass: the need-th largest key
-  uint32_t prefix = 0, mask = 0;
-  int remaining = need;
-  for (int shift = 24; shift >= 0; shift -= 8) {
+  wave_lds_fence();
+  select_row(keys, hist, lane, m, need, i, out);
+}
+
+// Scores and selection in one kernel: the scores of a row never leave the compute unit.  One
+// workgroup of 16 wavefronts owns R consecutive query blocks of the packed batch and one selection
+// head.  For each sequence that these blocks touch, every wavefront computes 16 x 16 score tiles
+// (the rows' pooled queries in registers, pooled keys straight from memory: they are small and stay
+// in L2) and leaves the order keys of the past blocks in LDS, row by row; after a barrier wavefront
+// w selects for row w exactly as topk_kernel does.  R (16, or fewer for very long sequences) is what
+// fits in LDS: R rows of `stride` keys plus one histogram per wavefront.
+constexpr int kFusedWaves = 16;
+
+template <int D>
+__global__ __launch_bounds__(64 * kFusedWaves) void score_select_kernel(
+    const float* __restrict__ qbar, const float* __restrict__ kbar, const int32_t* __restrict__ qb_off,
+    const int32_t* __restrict__ row_base, const int32_t* __restrict__ kclamp, const int32_t* __restrict__ qb_seq, int64_t NQB,
+    int Hq, int Hkv, int Hs, int G, int mode, float scale, int64_t nnz_unit, int R, int stride, int32_t* __restrict__ rowptr,
+    int32_t* __restrict__ idx) {
+  extern __shared__ uint32_t smem[];
+  uint32_t* keys = smem;                            // [R][stride]
+  int* hist = (int*)(smem + (size_t)R * stride);    // [kFusedWaves][256]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l16 = lane & 15, kq = lane >> 4;
+  const int hs = blockIdx.y;
+  const int heads = mode == SB_SELECT_PER_QHEAD ? 1 : G;
+  const int h0 = mode == SB_SELECT_PER_QHEAD ? hs : hs * G;
+  const int g = h0 / G;
+  // rows late in a sequence have the most past blocks: hand out the last groups of blocks first
+  const int64_t b0 = ((int64_t)gridDim.x - 1 - blockIdx.x) * R, b1 = min(NQB, b0 + R);
+  for (int64_t ba = b0; ba < b1;) {
+    const int s = qb_seq[ba];
+    const int64_t qb0 = qb_off[s];
+    const int n = qb_off[s + 1] - (int)qb0;
+    const int ia = (int)(ba - qb0), ib = (int)min((int64_t)n, ia + (b1 - ba));  // rows [ia, ib) of sequence s
+    const int nrows = ib - ia;
+    const int k = kclamp[s];
+    // a row needs its scores only if it keeps some but not all of its past blocks: 2 <= k <= i
+    if (k >= 2 && ib - 1 >= k) {
+      float a[D / 4];
 #pragma unroll
-    for (int a = 0; a < 4; ++a) hist[lane + 64 * a] = 0;
-    wave_lds_fence();
-    for (int j = lane; j < m; j += 64) {
-      const uint32_t kk = keys[j];
-      if ((kk & mask) == prefix) atomicAdd(&hist[(kk >> shift) & 255u], 1);
+      for (int t = 0; t < D / 4; ++t) a[t] = 0.f;
+      const int ra = min(ia + l16, ib - 1);  // rows past the segment repeat its last row; their results are dropped
+      for (int hh = 0; hh < heads; ++hh) add_quarter<D>(a, qbar + ((qb0 + ra) * Hq + h0 + hh) * D, kq);
+      const int ncol = ib - 1;  // block j is in the past of some row of the segment iff j < ib - 1
+      for (int ct = wave; ct * 16 < ncol; ct += kFusedWaves) {
+        const int j = ct * 16 + l16;
+        float b[D / 4];
+        load_quarter<D>(b, kbar + ((qb0 + min(j, n - 1)) * Hkv + g) * D, kq);
+        const f32x4s acc = score_tile16<D>(a, b);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int r = 4 * kq + v;
+          if (r < nrows && j < ia + r) keys[(size_t)r * stride + j] = order_key(scale * acc[v]);
+        }
+      }
     }
-    wave_lds_fence();
-    // lane L owns bins 255-4L .. 252-4L (descending); `above` = matching keys in higher bins
-    int v[4], sum = 0;
-#pragma unroll
-    for (int a = 0; a < 4; ++a) { v[a] = hist[255 - 4 * lane - a]; sum += v[a]; }
-    int incl = sum;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const int t = __shfl_up(incl, off, 64);
-      if (lane >= off) incl += t;
+    __syncthreads();
+    if (wave < nrows) {
+      const int i = ia + wave;
+      const int c = min(k, i + 1);
+      const int64_t row_id = (int64_t)hs * NQB + ba + wave;
+      const int64_t start = (int64_t)hs * nnz_unit + row_base[s] + sel_rows_before(i, k);
+      if (lane == 0) {
+        rowptr[row_id] = (int32_t)start;
+        if (row_id == (int64_t)Hs * NQB - 1) rowptr[(int64_t)Hs * NQB] = (int32_t)(start + c);
+      }
+      int32_t* out = idx + start;
+      const int need = c - 1, m = i;
+      if (need == m) {
+        for (int j = lane; j <= i; j += 64) out[j] = j;
+      } else if (need == 0) {
+        if (lane == 0) out[0] = i;
+      } else {
+        select_row(keys + (size_t)wave * stride, hist + 256 * wave, lane, m, need, i, out);
+      }
     }
-    int run = incl - sum, bin = -1, above = 0;
-#pragma unroll
-    for (int a = 0; a < 4; ++a) {
-      if (run < remaining && remaining <= run + v[a]) { bin = 255 - 4 * lane - a; above = run; }
-      run += v[a];
-    }
-    const unsigned long long found = __builtin_amdgcn_ballot_w64(bin >= 0);  // exactly one lane
-    const int src = __builtin_ctzll(found);
-    bin = __shfl(bin, src, 64);
-    above = __shfl(above, src, 64);
-    prefix |= (uint32_t)bin << shift;
-    mask |= 255u << shift;
-    remaining -= above;
-    wave_lds_fence();  // the histogram is cleared again at the top
+    __syncthreads();  // the keys are overwritten by the next segment
+    ba += nrows;
   }
-  // keys > prefix are all kept; of the keys == prefix the `remaining` lowest indices are kept; output in index order
-  const uint32_t thr = prefix;
-  const unsigned long long lt = (1ull << lane) - 1ull;
-  int eq_seen = 0, pos = 0;
-  for (int j0 = 0; j0 < m; j0 += 64) {
-    const int j = j0 + lane;
-    const bool valid = j < m;
-    const uint32_t kk = valid ? keys[j] : 0u;
-    const bool is_eq = valid && kk == thr;
-    const unsigned long long beq = __builtin_amdgcn_ballot_w64(is_eq);
-    const int eq_rank = eq_seen + __builtin_popcountll(beq & lt);
-    const bool keep = valid && (kk > thr || (is_eq && eq_rank < remaining));
-    const unsigned long long bk = __builtin_amdgcn_ballot_w64(keep);
-    if (keep) out[pos + __builtin_popcountll(bk & lt)] = j;
-    pos += __builtin_popcountll(bk);
-    eq_seen += __builtin_popcountll(beq);
-  }
-  if (lane == 0) out[need] = i;
 }
 
 }  // namespace sb
@@ -175,6 +186,52 @@ extern "C" int sb_select_topk(const sb_problem* p, const float* scores, int32_t*
   return select_launch(g, make_tables(g, p, ws), scores, sel_rowptr_out, sel_idx_out, st);
 }
 
+// launches the kernel that scores and selects; qbar/kbar are the pooled arrays
+static int score_select_launch(const Geo& g, const Tables& t, const float* qbar, const float* kbar, int32_t* sel_rowptr_out,
+                               int32_t* sel_idx_out, hipStream_t st) {
+  static std::mutex mu;
+  static int lds_of_device[kMaxDevices] = {};  // LDS a workgroup may use, once the kernels' limit has been raised to it
+  int dev = 0;
+  SB_CHECK_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) { set_error("device ordinal %d out of range", dev); return SB_ERR_UNSUPPORTED; }
+  int cap = 0;
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!lds_of_device[dev]) {
+      int per_block = 0;
+      SB_CHECK_HIP(hipDeviceGetAttribute(&per_block, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
+      SB_CHECK_HIP(hipFuncSetAttribute((const void*)score_select_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, per_block));
+      SB_CHECK_HIP(hipFuncSetAttribute((const void*)score_select_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, per_block));
+      lds_of_device[dev] = per_block;
+    }
+    cap = lds_of_device[dev];
+  }
+  // a row of keys is padded to a stride of 4 mod 16 words, so that the four query rows a store instruction touches
+  // fall into different banks
+  const int stride = (g.n_max + 63) / 64 * 64 + 4;
+  const size_t hist_words = 256 * (size_t)kFusedWaves;
+  int R = kFusedWaves;
+  while (R > 1 && sizeof(uint32_t) * ((size_t)R * stride + hist_words) > (size_t)cap) R >>= 1;
+  const size_t smem = sizeof(uint32_t) * ((size_t)R * stride + hist_words);
+  if (smem > (size_t)cap) {
+    set_error("a sequence of %d blocks does not fit the fused selection (%zu bytes of LDS, %d available): pass scores_out", g.n_max,
+              smem, cap);
+    return SB_ERR_UNSUPPORTED;
+  }
+  dim3 grid((unsigned)((g.NQB + R - 1) / R), (unsigned)g.Hs);
+  KernelTimer kt(K_SCORE_SELECT, st);
+  if (g.D == 128)
+    hipLaunchKernelGGL(score_select_kernel<128>, grid, dim3(64 * kFusedWaves), smem, st, qbar, kbar, t.qb_off, t.row_base, t.kclamp,
+                       t.qb_seq, g.NQB, g.Hq, g.Hkv, g.Hs, g.G, g.mode, g.score_scale, g.nnz_unit, R, stride, sel_rowptr_out,
+                       sel_idx_out);
+  else
+    hipLaunchKernelGGL(score_select_kernel<64>, grid, dim3(64 * kFusedWaves), smem, st, qbar, kbar, t.qb_off, t.row_base, t.kclamp,
+                       t.qb_seq, g.NQB, g.Hq, g.Hkv, g.Hs, g.G, g.mode, g.score_scale, g.nnz_unit, R, stride, sel_rowptr_out,
+                       sel_idx_out);
+  SB_LAUNCH_CHECK("score_select_kernel");
+  return SB_OK;
+}
+
 extern "C" int sb_score_select(const sb_problem* p, const void* q, const void* k, float* kbar_out, float* scores_out,
                                int32_t* sel_rowptr_out, int32_t* sel_idx_out, void* ws, void* stream) {
   Geo g;
@@ -186,9 +243,18 @@ extern "C" int sb_score_select(const sb_problem* p, const void* q, const void* k
     return fill_zero(sel_rowptr_out, sizeof(int32_t), st);
   }
   if (!sel_idx_out) { set_error("null sel_idx_out"); return SB_ERR_INVALID_ARG; }
-  rc = sb_block_scores(p, q, k, kbar_out, scores_out, ws, stream);  // leaves the geometry tables at the start of ws
+  if (scores_out) {  // the caller wants the score matrix: write it, then select from it
+    rc = sb_block_scores(p, q, k, kbar_out, scores_out, ws, stream);  // leaves the geometry tables at the start of ws
+    if (rc != SB_OK) return rc;
+    return select_launch(g, make_tables(g, p, ws), scores_out, sel_rowptr_out, sel_idx_out, st);
+  }
+  if (!q || !k || !ws) { set_error("null q, k or ws"); return SB_ERR_INVALID_ARG; }
+  rc = launch_geom(g, p, ws, st);
   if (rc != SB_OK) return rc;
-  return select_launch(g, make_tables(g, p, ws), scores_out, sel_rowptr_out, sel_idx_out, st);
+  Tables t = make_tables(g, p, ws);
+  float *qbar = nullptr, *kbar = nullptr;
+  if ((rc = launch_pool(g, p, t, q, k, kbar_out, ws, st, &qbar, &kbar)) != SB_OK) return rc;
+  return score_select_launch(g, t, qbar, kbar, sel_rowptr_out, sel_idx_out, st);
 }
 
 // ---------------------------------------------------------------------------------------------

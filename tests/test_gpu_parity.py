@@ -344,6 +344,54 @@ def test_score_select_in_one_call(mode):
     assert np.array_equal(rp, rowptr.cpu().numpy()) and np.array_equal(ix, idx.cpu().numpy()[: int(rp[-1])])
 
 
+def fused_selection_matches(r: Run):
+    """sb_score_select without a score buffer (one kernel, scores stay on chip) against the two calls of `r`."""
+    _, rowptr, idx = sb.sb_score_select(r.pb, r.q, r.k, want_scores=False)
+    torch.cuda.synchronize()
+    nnz = int(r.rowptr_h[-1])
+    assert torch.equal(rowptr, r.rowptr), "row pointers differ"
+    assert torch.equal(idx[:nnz], r.idx[:nnz]), "selected blocks differ"
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_fused_score_select_same_bits(mode):
+    """The single-kernel form selects the same blocks as sb_block_scores + sb_select_topk, bit for bit: ragged
+    sequences, sequences inside one group of 16 rows, both head widths, larger selection blocks, budgets from 1 block
+    to everything."""
+    cases = [synth.small_ragged(seed=71, lens=(700, 64, 1, 0, 130, 1500, 64 * 40 + 3), Hq=8, Hkv=2, D=128, ratio=(0.05, 0.9)),
+             synth.small_ragged(seed=72, lens=[1 + (53 * s) % 400 for s in range(60)], Hq=4, Hkv=2, D=64, ratio=(0.1, 1.0)),
+             synth.small_ragged(seed=73, lens=(256 * 37 + 9, 300, 256 * 18), Hq=6, Hkv=3, D=64, B=256, ratio=(0.1, 0.5)),
+             synth.Workload("budget1", [64 * 50, 64 * 20], 4, 1, 128, topk=[1, 2], seed=74),
+             synth.Workload("budget_all", [64 * 50 + 1, 64 * 20], 4, 4, 128, topk=[51, 19], seed=75)]
+    for w in cases:
+        r = Run(w, mode, do_bwd=False)
+        fused_selection_matches(r)
+        print(w, "mode", mode, "fused selection identical", flush=True)
+
+
+def test_fused_score_select_ties_and_long_rows():
+    """All-equal scores (zero queries): ties go to the lower block index in both forms.  A sequence of 2600 blocks: fewer
+    rows per workgroup in the fused kernel (its LDS holds 8 rows of that length, not 16)."""
+    w = synth.small_ragged(seed=76, lens=(64 * 300 + 5, 900), Hq=4, Hkv=2, D=128, ratio=(0.1, 0.3))
+    r = Run(w, sb.SB_SELECT_PER_QHEAD, do_bwd=False)
+    r.q.zero_()
+    r.scores = sb.sb_block_scores(r.pb, r.q, r.k)
+    r.rowptr, r.idx = sb.sb_select_topk(r.pb, r.scores)
+    torch.cuda.synchronize()
+    r.rowptr_h = r.rowptr.cpu().numpy()
+    idx_h = r.idx.cpu().numpy()
+    k0, n0 = int(min(r.topk[0], 301)), 301
+    row = n0 - 1                                             # last row of the first sequence, head 0
+    assert list(idx_h[r.rowptr_h[row]:r.rowptr_h[row + 1]]) == list(range(k0 - 1)) + [n0 - 1]
+    fused_selection_matches(r)
+    w = synth.Workload("long2600", [64 * 2600 - 7, 64 * 33], 2, 1, 64, keep_ratio=[0.01, 0.5], seed=77)
+    for mode in (0, 1):
+        r = Run(w, mode, do_bwd=False)
+        sc = check_scores(r)
+        check_selection(r, sc)
+        fused_selection_matches(r)
+
+
 @pytest.mark.parametrize("nblk", [8200, 12500])
 def test_more_than_8192_blocks_in_one_sequence(nblk):
     """A sequence of 8200 blocks (524 800 tokens): more columns than one pass of the plan's transpose holds, one row per
@@ -353,5 +401,6 @@ def test_more_than_8192_blocks_in_one_sequence(nblk):
     r = Run(w, sb.SB_SELECT_PER_QHEAD)
     sc = check_scores(r)
     check_selection(r, sc)
+    fused_selection_matches(r)
     check_plan(r)
     print(w, check_attention(r), flush=True)
