@@ -77,12 +77,17 @@ __global__ __launch_bounds__(64 * kFusedWaves) void score_select_kernel(
   uint32_t* keys = smem;                            // [R][stride]
   int* hist = (int*)(smem + (size_t)R * stride);    // [kFusedWaves][256]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l16 = lane & 15, kq = lane >> 4;
-  const int hs = blockIdx.y;
+  // Workgroup ids run over the selection heads first and workgroups go to the eight XCDs in turn: head index
+  // (x % 8) * (Hs / 8) + x / 8 gives every XCD a contiguous range of heads, i.e. few KV heads, whose pooled keys
+  // (n * D floats each) then stay in that XCD's L2.
+  const int hx = blockIdx.x % Hs;
+  const int64_t gy = blockIdx.x / Hs, ngroups = gridDim.x / Hs;
+  const int hs = (Hs & 7) == 0 ? (hx & 7) * (Hs >> 3) + (hx >> 3) : hx;
   const int heads = mode == SB_SELECT_PER_QHEAD ? 1 : G;
   const int h0 = mode == SB_SELECT_PER_QHEAD ? hs : hs * G;
   const int g = h0 / G;
   // rows late in a sequence have the most past blocks: hand out the last groups of blocks first
-  const int64_t b0 = ((int64_t)gridDim.x - 1 - blockIdx.x) * R, b1 = min(NQB, b0 + R);
+  const int64_t b0 = (ngroups - 1 - gy) * R, b1 = min(NQB, b0 + R);
   for (int64_t ba = b0; ba < b1;) {
     const int s = qb_seq[ba];
     const int64_t qb0 = qb_off[s];
@@ -218,7 +223,9 @@ static int score_select_launch(const Geo& g, const Tables& t, const float* qbar,
               smem, cap);
     return SB_ERR_UNSUPPORTED;
   }
-  dim3 grid((unsigned)((g.NQB + R - 1) / R), (unsigned)g.Hs);
+  const int64_t groups = (g.NQB + R - 1) / R;
+  if (groups * g.Hs > 0x7fffffffll) { set_error("too many rows for one launch of the fused selection: pass scores_out"); return SB_ERR_UNSUPPORTED; }
+  dim3 grid((unsigned)(groups * g.Hs));
   KernelTimer kt(K_SCORE_SELECT, st);
   if (g.D == 128)
     hipLaunchKernelGGL(score_select_kernel<128>, grid, dim3(64 * kFusedWaves), smem, st, qbar, kbar, t.qb_off, t.row_base, t.kclamp,

@@ -361,6 +361,7 @@ def test_fused_score_select_same_bits(mode):
     cases = [synth.small_ragged(seed=71, lens=(700, 64, 1, 0, 130, 1500, 64 * 40 + 3), Hq=8, Hkv=2, D=128, ratio=(0.05, 0.9)),
              synth.small_ragged(seed=72, lens=[1 + (53 * s) % 400 for s in range(60)], Hq=4, Hkv=2, D=64, ratio=(0.1, 1.0)),
              synth.small_ragged(seed=73, lens=(256 * 37 + 9, 300, 256 * 18), Hq=6, Hkv=3, D=64, B=256, ratio=(0.1, 0.5)),
+             synth.small_ragged(seed=78, lens=(64 * 30 + 1, 300), Hq=16, Hkv=4, D=64, ratio=(0.1, 0.5)),   # 16 selection heads: permuted over the XCDs
              synth.Workload("budget1", [64 * 50, 64 * 20], 4, 1, 128, topk=[1, 2], seed=74),
              synth.Workload("budget_all", [64 * 50 + 1, 64 * 20], 4, 4, 128, topk=[51, 19], seed=75)]
     for w in cases:
