@@ -33,9 +33,10 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1))) void a
   // Workgroup id -> (position in the work list, query head of the group).  In per-KV-group mode the
   // `heads` query heads of an item take ids that are 8 apart, so they run on the same XCD (ids are
   // dealt round-robin to the 8 XCDs) and share its L2 for the K/V strips.
-  const int pos = (int)(blockIdx.x / (8u * heads)) * 8 + (int)(blockIdx.x & 7u);
-  if (pos >= n_items) return;
+  int pos = (int)(blockIdx.x / (8u * heads)) * 8 + (int)(blockIdx.x & 7u);
   const int hh = (int)(blockIdx.x >> 3) % heads;
+  pos = claim_item(pos, n_items, P.ticket ? P.ticket + hh : nullptr);
+  if (pos < 0) return;
   const WorkItem item = P.items[pos];
   const int hs = item.hs, i = item.i, L = item.len, e0 = item.e0, ntiles = item.ntiles;
   const int64_t seq0 = item.seq0;
@@ -362,7 +363,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2))) void a
   timer.start(P);
   const int tid = threadIdx.x, nthr = blockDim.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-  const WorkItem item = P.items[blockIdx.x];
+  const int pos = claim_item(blockIdx.x, P.n_items, P.ticket ? P.ticket + blockIdx.y : nullptr);
+  if (pos < 0) return;
+  const WorkItem item = P.items[pos];
   const int hs = item.hs, i = item.i, L = item.len, e0 = item.e0, ntiles = item.ntiles;
   const int64_t seq0 = item.seq0;
   const int strip = wave & 1;
@@ -609,11 +612,18 @@ extern "C" int sb_sparse_attn_fwd(const sb_problem* p, const void* q, const void
   }
   const int heads = g.mode == SB_SELECT_PER_QHEAD ? 1 : g.G;  // query heads that share a work item
   const int64_t n_items = (int64_t)g.Hs * g.NQB;
+  if (n_items > 0x3fffffffll) { set_error("too many work items for one launch"); return SB_ERR_INVALID_ARG; }
   const int parts = (heads + 3) / 4, hpp = (heads + parts - 1) / parts;  // the group kernel takes `hpp` heads per workgroup
+  const bool tickets = use_tickets(n_items) && heads <= kTicketSlots;
+  P.n_items = (int)n_items; P.ticket = nullptr;
   KernelTimer kt(K_FWD, st);
+  if (tickets) {
+    P.ticket = (int*)(wb + wo.ticket);
+    if ((rc = fill_zero(P.ticket, sizeof(int32_t) * kTicketSlots, st)) != SB_OK) return rc;
+  }
+  const int64_t n_slots = ticketed_grid(n_items, tickets);  // workgroups per head plane
   if (hpp >= 3 && parts * hpp == heads) {  // heads share K/V tiles in LDS; with a head slot left idle the per-head kernel is faster
-    if (n_items > 0x7fffffffll) { set_error("too many work items for one launch"); return SB_ERR_INVALID_ARG; }
-    dim3 grid((unsigned)n_items, (unsigned)parts), block(128 * hpp);
+    dim3 grid((unsigned)n_slots, (unsigned)parts), block(128 * hpp);
 #define SB_FWD_LAUNCH(DD, FF) hipLaunchKernelGGL((attn_fwd_group_kernel<DD, FF>), grid, block, 0, st, P, heads)
     if (g.D == 128) {
       if (P.out_f32) SB_FWD_LAUNCH(128, true); else SB_FWD_LAUNCH(128, false);
@@ -622,7 +632,7 @@ extern "C" int sb_sparse_attn_fwd(const sb_problem* p, const void* q, const void
     }
 #undef SB_FWD_LAUNCH
   } else {
-    const int64_t n_wg = (n_items + 7) / 8 * 8 * heads;
+    const int64_t n_wg = n_slots * heads;
     if (n_wg > 0x7fffffffll) { set_error("too many work items for one launch"); return SB_ERR_INVALID_ARG; }
     dim3 grid((unsigned)n_wg), block(128);
 #define SB_FWD_LAUNCH(DD, FF) hipLaunchKernelGGL((attn_fwd_kernel<DD, FF>), grid, block, 0, st, P, (int)n_items, heads)

@@ -15,6 +15,8 @@
 //                           blocks, then C_s(k) = (Hs*k + sum_{i>=k} Pacc[s][i][k-2]) / (Hs*n) (the k rows i < k are fully covered)
 #include <math.h>
 
+#include <mutex>
+
 #include "sb_internal.h"
 
 namespace sb {
@@ -234,12 +236,17 @@ int sb_score_coverage(const sb_problem* p, const float* scores, float* coverage_
   int N = 1;
   while (N < g.n_max) N <<= 1;
   const size_t smem = sizeof(float) * (size_t)(2 * N + 264);
-  if (smem > 48 * 1024) {
-    static bool attr_set = false;
-    if (!attr_set) {
+  if (smem > 48 * 1024) {  // raise the kernel's dynamic LDS limit; once per device, whichever thread comes first
+    static std::mutex mu;
+    static bool attr_set[kMaxDevices] = {};
+    int dev = 0;
+    SB_CHECK_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) { set_error("device ordinal %d out of range", dev); return SB_ERR_UNSUPPORTED; }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!attr_set[dev]) {
       SB_CHECK_HIP(hipFuncSetAttribute((const void*)coverage_rows_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)(sizeof(float) * (2 * SB_MAX_BLOCKS_PER_SEQ + 264))));
-      attr_set = true;
+      attr_set[dev] = true;
     }
   }
   KernelTimer kt(K_COVERAGE, st);

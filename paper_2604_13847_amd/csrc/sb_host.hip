@@ -190,11 +190,13 @@ static WsOffsets ws_offsets(const Geo& g, bool bwd) {
   w.doc = o; o = align_up(o + (bwd ? qbytes : 0));
   w.drow = o; o = align_up(o + (bwd ? sizeof(float) * (size_t)g.T * g.Hq : 0));
   w.lse2 = o; o = align_up(o + (bwd ? sizeof(float) * ((size_t)g.T * g.Hq + 1) : 0));  // + one +inf sentinel
+  w.ticket = o; o = align_up(o + sizeof(int32_t) * 64);
   w.partials = o; o = align_up(o + (bwd ? sizeof(float) * 2 * (size_t)split_extra_max(tile_geo(g)) * 2 * 64 * g.D : 0));  // tile_geo is idempotent
   w.bytes = o;
   return w;
 }
 WsOffsets fwd_ws_offsets(const Geo& g) { return ws_offsets(g, false); }
+
 WsOffsets bwd_ws_offsets(const Geo& g) { return ws_offsets(g, true); }
 
 size_t scores_ws_bytes(const Geo& g) {
