@@ -7,10 +7,13 @@
 // j < i; their scores are normalised by a softmax and sorted in descending order; a budget k keeps
 // the diagonal block and the k-1 best candidates, so the row covers pref_i[min(k-1, i)], the sum of
 // its min(k-1, i) largest shares (pref_i[i] = 1).  C_s(k) is the mean over the sequence's rows.
-// Two kernels, both deterministic (fixed summation order, no atomics):
-//   coverage_rows_kernel    one workgroup per query block (s, i) and group of selection heads: for every head in turn,
-//                           softmax + bitonic sort + prefix sum in LDS, summed over heads into
+// All kernels are deterministic (fixed summation order, no atomics):
+//   coverage_rows_regs_kernel   rows of at most 2048 candidates: one wavefront per (row, selection head) sorts the row in
+//                           registers (bitonic network, cross-lane permutes only at distances of a lane's share and
+//                           above), then softmax and prefix sums; summed over the heads of a group into
 //                           Pacc[s][i][m-1] = sum_hs pref_{hs,i}[m], m = 1..i
+//   coverage_rows_kernel    longer rows: one workgroup per query block and group of selection heads, for every head in
+//                           turn softmax + bitonic sort + prefix sum in LDS, into the same Pacc
 //   coverage_partial_kernel / coverage_reduce_kernel   one thread per (s, k): column sums of Pacc over slabs of 32 query
 //                           blocks, then C_s(k) = (Hs*k + sum_{i>=k} Pacc[s][i][k-2]) / (Hs*n) (the k rows i < k are fully covered)
 #include <math.h>
@@ -35,16 +38,38 @@ __device__ inline float block_reduce_256(float v, float* tmp, bool is_max) {
   return r;  // the same value, combined in the same order, in every thread
 }
 
+// P compare-exchanges of one bitonic stage per lane (pairs t, t + 64, ...): the pairs of a stage are disjoint, so all
+// operands are read before anything is written back and the LDS latencies of the P pairs overlap.
+template <int P>
+__device__ inline void bitonic_pairs(float* keys, int t0, int j2, int k2) {
+  int lo[P];
+  float a[P], b[P];
+#pragma unroll
+  for (int u = 0; u < P; ++u) {
+    const int t = t0 + 64 * u;
+    lo[u] = ((t & ~(j2 - 1)) << 1) | (t & (j2 - 1));  // j2 is a power of two
+    a[u] = keys[lo[u]];
+    b[u] = keys[lo[u] + j2];
+  }
+#pragma unroll
+  for (int u = 0; u < P; ++u) {  // branch-free: both elements are written back, swapped or not
+    const bool lt = a[u] < b[u], gt = a[u] > b[u];
+    const bool swap = (lo[u] & k2) == 0 ? lt : gt;
+    keys[lo[u]] = swap ? b[u] : a[u];
+    keys[lo[u] + j2] = swap ? a[u] : b[u];
+  }
+}
+
 __global__ __launch_bounds__(256) void coverage_rows_kernel(const float* __restrict__ scores, const int32_t* __restrict__ qb_off,
                                                             const int64_t* __restrict__ sc_off, const int32_t* __restrict__ qb_seq,
-                                                            int Hs, int64_t slab, float* __restrict__ pacc) {
+                                                            int Hs, int64_t slab, int min_row, float* __restrict__ pacc) {
   extern __shared__ float smem[];  // keys[N], acc[N], tmp[260]
   const int tid = threadIdx.x;
   const int qb = blockIdx.x;
   const int s = qb_seq[qb];
   const int i = qb - qb_off[s];
   const int n = qb_off[s + 1] - qb_off[s];
-  if (i == 0) return;  // no candidates: the row is fully covered at every budget
+  if (i == 0 || i < min_row) return;  // no candidates: the row is fully covered at every budget; short rows: the other kernel's
   int N = 1;
   while (N < i) N <<= 1;
   float* keys = smem;
@@ -78,19 +103,13 @@ __global__ __launch_bounds__(256) void coverage_rows_kernel(const float* __restr
           if (shared || shared_prev) __syncthreads(); else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
           shared_prev = shared;
           if (N < 512) {
-            for (int t = tid; t < (N >> 1); t += 256) {
-              const int lo = ((t & ~(j2 - 1)) << 1) | (t & (j2 - 1)), hi = lo + j2;  // j2 is a power of two
-              const bool desc = (lo & k2) == 0;
-              const float a = keys[lo], b = keys[hi];
-              if (desc ? a < b : a > b) { keys[lo] = b; keys[hi] = a; }
-            }
-          } else {
-            for (int t = wave * ppw + lane; t < (wave + 1) * ppw; t += 64) {
-              const int lo = ((t & ~(j2 - 1)) << 1) | (t & (j2 - 1)), hi = lo + j2;  // j2 is a power of two
-              const bool desc = (lo & k2) == 0;
-              const float a = keys[lo], b = keys[hi];
-              if (desc ? a < b : a > b) { keys[lo] = b; keys[hi] = a; }
-            }
+            if (tid < (N >> 1)) bitonic_pairs<1>(keys, tid, j2, k2);  // at most 128 pairs
+          } else if (ppw == 64) {
+            bitonic_pairs<1>(keys, wave * ppw + lane, j2, k2);
+          } else if (ppw == 128) {
+            bitonic_pairs<2>(keys, wave * ppw + lane, j2, k2);
+          } else {  // a multiple of 256 pairs per wavefront
+            for (int t = wave * ppw + lane; t < (wave + 1) * ppw; t += 256) bitonic_pairs<4>(keys, t, j2, k2);
           }
         }
       }
@@ -129,6 +148,138 @@ __global__ __launch_bounds__(256) void coverage_rows_kernel(const float* __restr
   }
   float* out = pacc + (int64_t)blockIdx.y * slab + sc_off[s] + (int64_t)i * n;
   for (int j = tid; j < i; j += 256) out[j] = acc[j];
+}
+
+// The same rows for sequences of at most kCovRegMax blocks, sorted in registers: one wavefront per (row, selection
+// head), 64 E = N keys (N the row length rounded up to a power of two, at least 64), E per lane.  Key number lane * E + r
+// of the bitonic network lives in register r of the lane, so the compare-exchanges at distances below E stay inside a lane
+// (two instructions per pair, no memory) and only those at distances E and above cross lanes (one permute each); a
+// wavefront alone needs no barrier.  A block of the network that sorts ascending is handled by negating its lanes' keys,
+// so that every compare-exchange puts the larger key first.  The four wavefronts of a workgroup take the heads of the
+// group in turn, keep their sums in registers and add them in wavefront order at the end: fixed summation order again.
+// Scores must be numbers (a NaN is dropped by the max/min of a compare-exchange); sb_block_scores writes none for finite
+// inputs.
+constexpr int kCovRegMax = 2048;
+
+template <int E>
+__device__ __forceinline__ void coverage_row_regs(const float* __restrict__ row, int i, int lane, float (&acc)[E]) {
+  float x[E];
+#pragma unroll
+  for (int r = 0; r < E; ++r) x[r] = r * 64 + lane < i ? row[r * 64 + lane] : -INFINITY;  // any initial placement will do
+  // phases k2 = 2 .. E/2: inside a lane, directions known at compile time (bit k2 of r)
+#pragma unroll
+  for (int k2 = 2; k2 < E; k2 <<= 1) {
+#pragma unroll
+    for (int j2 = k2 >> 1; j2 > 0; j2 >>= 1) {
+#pragma unroll
+      for (int r = 0; r < E; ++r) {
+        if ((r & j2) == 0) {
+          const float hi = fmaxf(x[r], x[r | j2]), lo = fminf(x[r], x[r | j2]);
+          const bool desc = (r & k2) == 0;
+          x[r] = desc ? hi : lo;
+          x[r | j2] = desc ? lo : hi;
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);  // (left alone, the scheduler interleaves the stages and triples the register count)
+    }
+  }
+  // phases k2 = E .. 64 E: the direction is bit k2 / E of the lane; ascending lanes work on negated keys
+  bool negated = false;
+#pragma unroll 1
+  for (int t = (E > 1 ? 0 : 1); t <= 6; ++t) {
+    const bool want = ((lane >> t) & 1) != 0 && t < 6;  // (the last phase, k2 = N, is descending everywhere)
+    const uint32_t flip = want != negated ? 0x80000000u : 0u;
+    negated = want;
+#pragma unroll
+    for (int r = 0; r < E; ++r) x[r] = __uint_as_float(__float_as_uint(x[r]) ^ flip);
+    for (int d = (1 << t) >> 1; d > 0; d >>= 1) {  // distances d * E: lane l against lane l ^ d
+      const int partner = (lane ^ d) << 2;
+      const bool first = (lane & d) == 0;
+      constexpr int C = E < 8 ? E : 8;  // registers exchanged at a time (keeps the values in flight few)
+#pragma unroll
+      for (int r0 = 0; r0 < E; r0 += C) {
+        float y[C];
+#pragma unroll
+        for (int r = 0; r < C; ++r) y[r] = __int_as_float(__builtin_amdgcn_ds_bpermute(partner, __float_as_int(x[r0 + r])));
+#pragma unroll
+        for (int r = 0; r < C; ++r) {
+          const float hi = fmaxf(x[r0 + r], y[r]), lo = fminf(x[r0 + r], y[r]);
+          x[r0 + r] = first ? hi : lo;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+#pragma unroll
+    for (int j2 = E >> 1; j2 > 0; j2 >>= 1) {
+#pragma unroll
+      for (int r = 0; r < E; ++r) {
+        if ((r & j2) == 0) {
+          const float hi = fmaxf(x[r], x[r | j2]), lo = fminf(x[r], x[r | j2]);
+          x[r] = hi;
+          x[r | j2] = lo;
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  // shares in sorted order (key 0 is the row maximum), their running sum, the coverage of every prefix
+  const float mx = __shfl(x[0], 0, 64);
+  float run = 0.f;
+#pragma unroll
+  for (int r = 0; r < E; ++r) {
+    x[r] = lane * E + r < i ? __expf(x[r] - mx) : 0.f;
+    run += x[r];
+  }
+  float incl = run;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const float up = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += up;
+  }
+  const float inv = 1.0f / __shfl(incl, 63, 64);
+  run = incl - run;  // the shares of the lanes before this one
+#pragma unroll
+  for (int r = 0; r < E; ++r) {
+    const int p = lane * E + r;
+    run += x[r];
+    if (p < i) acc[r] += p == i - 1 ? 1.0f : run * inv;
+  }
+}
+
+template <int E>
+__device__ __forceinline__ void coverage_rows_regs_body(const float* __restrict__ scores_s, int n, int i, int hs0, int hs1, float* part,
+                                               float* __restrict__ out) {
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  float acc[E];
+#pragma unroll
+  for (int r = 0; r < E; ++r) acc[r] = 0.f;
+  for (int hs = hs0 + wave; hs < hs1; hs += 4) coverage_row_regs<E>(scores_s + ((int64_t)hs * n + i) * n, i, lane, acc);
+#pragma unroll
+  for (int r = 0; r < E; ++r) part[wave * kCovRegMax + lane * E + r] = acc[r];
+  __syncthreads();
+  for (int p = tid; p < i; p += 256)
+    out[p] = ((part[p] + part[kCovRegMax + p]) + part[2 * kCovRegMax + p]) + part[3 * kCovRegMax + p];
+}
+
+__global__ __launch_bounds__(256) void coverage_rows_regs_kernel(const float* __restrict__ scores, const int32_t* __restrict__ qb_off,
+                                                                 const int64_t* __restrict__ sc_off, const int32_t* __restrict__ qb_seq,
+                                                                 int Hs, int64_t slab, float* __restrict__ pacc) {
+  __shared__ float part[4 * kCovRegMax];
+  const int qb = blockIdx.x;
+  const int s = qb_seq[qb];
+  const int i = qb - qb_off[s];
+  const int n = qb_off[s + 1] - qb_off[s];
+  if (i == 0 || i > kCovRegMax) return;  // no candidates; longer rows are left to coverage_rows_kernel
+  const int hpg = (Hs + (int)gridDim.y - 1) / (int)gridDim.y;  // selection heads per group
+  const int hs0 = blockIdx.y * hpg, hs1 = min(Hs, hs0 + hpg);
+  const float* scores_s = scores + (int64_t)Hs * sc_off[s];
+  float* out = pacc + (int64_t)blockIdx.y * slab + sc_off[s] + (int64_t)i * n;
+  if (i <= 64) coverage_rows_regs_body<1>(scores_s, n, i, hs0, hs1, part, out);
+  else if (i <= 128) coverage_rows_regs_body<2>(scores_s, n, i, hs0, hs1, part, out);
+  else if (i <= 256) coverage_rows_regs_body<4>(scores_s, n, i, hs0, hs1, part, out);
+  else if (i <= 512) coverage_rows_regs_body<8>(scores_s, n, i, hs0, hs1, part, out);
+  else if (i <= 1024) coverage_rows_regs_body<16>(scores_s, n, i, hs0, hs1, part, out);
+  else coverage_rows_regs_body<32>(scores_s, n, i, hs0, hs1, part, out);
 }
 
 // partial column sums over slabs of kCovSlab query blocks: part[y][qb] = sum over head groups and rows i of slab y, i >= k
@@ -252,9 +403,14 @@ int sb_score_coverage(const sb_problem* p, const float* scores, float* coverage_
   KernelTimer kt(K_COVERAGE, st);
   const int groups = coverage_groups(g);
   const int64_t slab = (int64_t)coverage_slab(g);
-  hipLaunchKernelGGL(coverage_rows_kernel, dim3((unsigned)g.NQB, (unsigned)groups), dim3(256), smem, st, scores, t.qb_off, t.sc_off,
+  hipLaunchKernelGGL(coverage_rows_regs_kernel, dim3((unsigned)g.NQB, (unsigned)groups), dim3(256), 0, st, scores, t.qb_off, t.sc_off,
                      t.qb_seq, g.Hs, slab, pacc);
-  SB_LAUNCH_CHECK("coverage_rows_kernel");
+  SB_LAUNCH_CHECK("coverage_rows_regs_kernel");
+  if (g.n_max > kCovRegMax + 1) {  // rows with more than kCovRegMax candidates
+    hipLaunchKernelGGL(coverage_rows_kernel, dim3((unsigned)g.NQB, (unsigned)groups), dim3(256), smem, st, scores, t.qb_off, t.sc_off,
+                       t.qb_seq, g.Hs, slab, kCovRegMax + 1, pacc);
+    SB_LAUNCH_CHECK("coverage_rows_kernel");
+  }
   float* part = pacc + slab * groups;
   hipLaunchKernelGGL(coverage_partial_kernel, dim3((unsigned)((g.NQB + 255) / 256), (unsigned)coverage_row_slabs(g)), dim3(256), 0, st, pacc,
                      t.qb_off, t.sc_off, t.qb_seq, g.NQB, groups, slab, part);

@@ -68,6 +68,18 @@ def test_coverage_ties_wide_range_and_long_rows():
     assert np.abs(got - ref).max() <= TOL
 
 
+def test_coverage_rows_on_both_sides_of_the_register_sort():
+    """Rows of up to 2048 candidates are sorted in registers, longer ones in LDS: sequences of 2100 and 2050 blocks have
+    rows of both kinds, the 3-head group leaves a wavefront of the register kernel without a head, and the short
+    sequences use every register count (1 .. 32 keys per lane)."""
+    w = synth.Workload("both", [2100 * 64 - 3, 2050 * 64, 65 * 64, 130 * 64, 300 * 64, 600 * 64, 1100 * 64], 3, 3, 64, topk=[16] * 7, seed=12)
+    pb, po, got, ref, _ = _curves(w, 0)
+    assert np.abs(got - ref).max() <= TOL
+    for s, n in enumerate(po.nblk):
+        C = got[po.qb_off[s]: po.qb_off[s] + n]
+        assert abs(C[0] - 1.0 / n) <= 1e-7 and abs(C[-1] - 1.0) <= 1e-7 and np.all(np.diff(C) >= -1e-7)
+
+
 @pytest.mark.parametrize("anchor", [0, 1, 2])
 def test_tuned_budgets_end_to_end(anchor):
     # budgets from the GPU's curves drive the attention path: the tuned problem runs and matches the checker's decision
