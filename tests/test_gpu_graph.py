@@ -12,8 +12,14 @@ from paper_2604_13847_amd import synth
 pytestmark = pytest.mark.gpu
 
 
-def test_captured_step_replays_bitwise():
-    w = synth.small_ragged(seed=2, lens=(700, 64, 1, 2100, 333), Hq=8, Hkv=2, D=128, ratio=(0.2, 0.6))
+@pytest.mark.parametrize("case", ["small", "ticketed"])
+def test_captured_step_replays_bitwise(case):
+    """"ticketed": more than 4096 query-major items, so the forward and dQ launches hand the tail of their work list out
+    through a ticket counter that a fill kernel clears in every step; this step also scores and selects in one kernel."""
+    if case == "small":
+        w = synth.small_ragged(seed=2, lens=(700, 64, 1, 2100, 333), Hq=8, Hkv=2, D=128, ratio=(0.2, 0.6))
+    else:
+        w = synth.small_ragged(seed=4, lens=(64 * 520 - 9, 700, 1), Hq=8, Hkv=2, D=64, ratio=(0.03, 0.08))
     topk = sb.sb_keep_ratio_to_topk(w.cu, w.B, w.keep_ratio)
     pb = sb.Problem(w.cu, topk, w.Hq, w.Hkv, w.D, w.B, device=DEV)
     lay = pb.layout
@@ -33,8 +39,11 @@ def test_captured_step_replays_bitwise():
 
     def step():
         st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
-        rc = L.sb_block_scores(pb.ref(), P(q), P(k), None, P(scores), P(ws[0]), st)
-        rc |= L.sb_select_topk(pb.ref(), P(scores), P(rowptr), P(idx), P(ws[1]), st)
+        if case == "small":
+            rc = L.sb_block_scores(pb.ref(), P(q), P(k), None, P(scores), P(ws[0]), st)
+            rc |= L.sb_select_topk(pb.ref(), P(scores), P(rowptr), P(idx), P(ws[1]), st)
+        else:
+            rc = L.sb_score_select(pb.ref(), P(q), P(k), None, None, P(rowptr), P(idx), P(ws[0]), st)
         rc |= L.sb_plan_worklist(pb.ref(), P(rowptr), P(idx), P(plan), st)
         rc |= L.sb_sparse_attn_fwd(pb.ref(), P(q), P(k), P(v), P(rowptr), P(idx), P(plan), P(bufs["o"]), P(bufs["lse"]), P(ws[2]), st)
         rc |= L.sb_sparse_attn_bwd(pb.ref(), P(q), P(k), P(v), P(bufs["o"]), P(bufs["lse"]), P(do), P(rowptr), P(idx), P(plan),
