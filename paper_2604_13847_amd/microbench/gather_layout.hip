@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdio.h>
 #include <stdint.h>
+#include <stdlib.h>
 #define CK(x) do { hipError_t e = (x); if (e != hipSuccess) { printf("%s: %s\n", #x, hipGetErrorString(e)); return 1; } } while (0)
 
 __device__ inline uint32_t mix(uint32_t x) { x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16; return x; }
@@ -46,9 +47,10 @@ static int run(const char* name, const uint4* buf, int T, int H, uint32_t* out) 
   return 0;
 }
 
-int main() {
+int main(int argc, char** argv) {
+  const int shift = argc > 1 ? atoi(argv[1]) : 0;   // buffer = 2 GiB >> shift
   for (int H : {8, 32}) {
-    const int T = H == 8 ? 1 << 20 : 1 << 18;     // 2 GiB either way
+    const int T = (H == 8 ? 1 << 20 : 1 << 18) >> shift;
     const size_t bytes = (size_t)T * H * 256;
     uint4* buf; uint32_t* out;
     CK(hipMalloc(&buf, bytes)); CK(hipMalloc(&out, 256));
