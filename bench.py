@@ -220,6 +220,18 @@ def run(workload, mode_name, seed, steps, warmup, selection="topk", cu_busy=True
         kt = sb.sb_read_kernel_times()
         sb.sb_set_instrumentation(0)
         nnz = int(lay.sel_nnz)
+        # likewise outside the step: the coverage curves of the budget controller (Eq. 4) from the scores of the last step
+        ws_cov = raw(lay.coverage_ws_bytes)
+        sb.sb_score_coverage(pb, scores, ws=ws_cov)
+        torch.cuda.synchronize()
+        sb.sb_set_instrumentation(sb.SB_INSTR_KERNEL_EVENTS)
+        for _ in range(3):
+            sb.sb_score_coverage(pb, scores, ws=ws_cov)
+        torch.cuda.synchronize()
+        kc = sb.sb_read_kernel_times()
+        sb.sb_set_instrumentation(0)
+        del ws_cov
+        res["score_coverage_ms"] = round(kc["coverage"][0] / 3, 4)
         res["fused_score_select"] = {"kernel_ms": round(kt["score_select"][0] / 5, 4),
                                      "two_kernel_ms": round(k_step["score"] + k_step["topk"], 4),
                                      "identical_selection": bool(torch.equal(rp2, rowptr) and torch.equal(ix2[:nnz], idx[:nnz]))}
@@ -296,7 +308,7 @@ def main():
         "kernel_ms": r["kernel_ms"], "kernel_tflops": r["kernel_tflops"], "roofline": r["roofline"], "hbm": r["hbm"],
         "cold_cache": r["cold_cache"],
     }
-    for key in ("fused_score_select", "cu_busy", "cpu_baseline"):
+    for key in ("fused_score_select", "score_coverage_ms", "cu_busy", "cpu_baseline"):
         if key in r:
             out[key] = r[key]
     if not args.no_also and args.selection == "topk":
