@@ -818,7 +818,7 @@ extern "C" int sb_sparse_attn_bwd(const sb_problem* p, const void* q, const void
     if ((rc = fill_zero(wb + wo.cu_busy, sizeof(uint64_t) * SB_CU_SLOTS, st)) != SB_OK) return rc;
     P.cu_busy = (unsigned long long*)(wb + wo.cu_busy);
   }
-  // The query-major launch hands one item in eight out by ticket (see claim_item).  The key-major launch does not: its
+  // The query-major launch hands one item in sixteen out by ticket (see claim_item).  The key-major launch does not: its
   // items are few and very unequal, and a heavy one that is held back for the tail lengthens the launch (measured: +23 %
   // on the 32768-token batch, -1 % on the 262144-token one).
   const int heads = g.mode == SB_SELECT_PER_QHEAD ? 1 : g.G;

@@ -42,7 +42,7 @@ constexpr int kTicketSlots = 64;    // one counter per head plane of a query-maj
 // Workgroup ids are dealt to the 8 XCDs in turn, so every XCD gets the same number of workgroups whatever its pace, and
 // the XCDs do differ by several percent (the L2 hit rate depends on which heads an XCD serves, and the dies themselves
 // differ): a launch that ties every item to a position ends when the slowest XCD is through its share.  So one item in
-// eight (the last 8 of every 64 in list order, a cross-section of the whole list) is held back: the other items are
+// sixteen (the last 8 of every 128 in list order, a cross-section of the whole list) is held back: the other items are
 // tied to the leading positions, in list order and on the XCD they would have had anyway, and the held-back ones form
 // the tail of the launch, handed out by ticket to whichever workgroup asks first.  The launch has twice as many tail
 // workgroups as tail items: a fast XCD gets through more of them, and those that find the tail empty exit at once.
@@ -50,13 +50,13 @@ constexpr int kTicketSlots = 64;    // one counter per head plane of a query-maj
 // Returns the item's index in the list or -1; every thread of the workgroup must call it (it has a barrier).
 __device__ inline int claim_item(int pos, int n_items, int* counter) {
   if (!counter) return pos < n_items ? pos : -1;
-  const int groups = n_items >> 6, held = groups << 3;  // held-back items: indices 64 q + 56 .. 64 q + 63
-  if (pos < n_items - held) return pos < 56 * groups ? (pos / 56 << 6) + pos % 56 : pos + held;
+  const int groups = n_items >> 7, held = groups << 3;  // held-back items: indices 128 q + 120 .. 128 q + 127
+  if (pos < n_items - held) return pos < 120 * groups ? (pos / 120 << 7) + pos % 120 : pos + held;
   __shared__ int sh_claim;
   if (threadIdx.x == 0) sh_claim = atomicAdd(counter, 1);
   __syncthreads();
   const int t = sh_claim;
-  return t < held ? ((t >> 3) << 6) + 56 + (t & 7) : -1;
+  return t < held ? ((t >> 3) << 7) + 120 + (t & 7) : -1;
 }
 
 __device__ inline f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {

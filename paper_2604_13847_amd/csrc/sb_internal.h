@@ -162,11 +162,11 @@ struct WsOffsets {
 };
 WsOffsets fwd_ws_offsets(const Geo& g);
 WsOffsets bwd_ws_offsets(const Geo& g);
-// Workgroups to launch for a list of n items when one item in eight is handed out by ticket at the end of the launch
+// Workgroups to launch for a list of n items when one item in sixteen is handed out by ticket at the end of the launch
 // (see claim_item in sb_attn_common.h): two tail workgroups per held-back item, the total a multiple of 8.
 constexpr int64_t kTicketMinItems = 4096;  // shorter lists are dealt by position only
 inline bool use_tickets(int64_t n) { return n >= kTicketMinItems; }
-inline int64_t ticketed_grid(int64_t n, bool tickets) { return (n + (tickets ? (n >> 6) << 3 : 0) + 7) / 8 * 8; }
+inline int64_t ticketed_grid(int64_t n, bool tickets) { return (n + (tickets ? (n >> 7) << 3 : 0) + 7) / 8 * 8; }
 size_t scores_ws_bytes(const Geo& g);
 size_t coverage_ws_bytes(const Geo& g);
 
