@@ -344,6 +344,24 @@ def test_score_select_in_one_call(mode):
     assert np.array_equal(rp, rowptr.cpu().numpy()) and np.array_equal(ix, idx.cpu().numpy()[: int(rp[-1])])
 
 
+@pytest.mark.parametrize("mode,Hq,Hkv,lens", [(0, 8, 2, (64 * 300, 64 * 250 + 5)), (1, 8, 4, (64 * 560 - 3, 64 * 470))])
+def test_ticketed_launches_elementwise(mode, Hq, Hkv, lens):
+    """More than 4096 query-major items: the forward and dQ launches hand one item in sixteen out through a ticket
+    counter at the end of the launch.  Every output element is compared, so an item that no workgroup took, or that two
+    took, would show; per-query-head selection with one head per workgroup, and per-KV-group selection with the group's
+    two heads in one workgroup."""
+    w = synth.small_ragged(seed=81 + mode, lens=lens, Hq=Hq, Hkv=Hkv, D=64, ratio=(0.02, 0.04))
+    r = Run(w, mode)
+    assert r.pb.layout.sel_rows >= 4096
+    print(w, "mode", mode, check_attention(r), flush=True)
+    o2, lse2 = sb.sb_sparse_attn_fwd(r.pb, r.q, r.k, r.v, r.rowptr, r.idx, r.plan)       # same bits whoever draws which ticket
+    dq2, dk2, dv2 = sb.sb_sparse_attn_bwd(r.pb, r.q, r.k, r.v, r.o, r.lse, r.do, r.rowptr, r.idx, r.plan)
+    torch.cuda.synchronize()
+    for a, b in ((o2, r.o), (dq2, r.dq), (dk2, r.dk), (dv2, r.dv)):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    assert torch.equal(lse2, r.lse)
+
+
 def fused_selection_matches(r: Run):
     """sb_score_select without a score buffer (one kernel, scores stay on chip) against the two calls of `r`."""
     _, rowptr, idx = sb.sb_score_select(r.pb, r.q, r.k, want_scores=False)
