@@ -9,39 +9,48 @@ namespace sb {
 
 __device__ inline float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
 
-// Mean over the valid tokens of one block, for 4 adjacent columns per thread.
-// grid = (NQB, ceil(H*D / 1024)); X is [T][H*D]; out is [NQB][H*D] float.
+// Mean over the valid tokens of one block, for 8 (bf16) or 4 (float) adjacent columns per thread: 16-byte loads, eight
+// rows in flight per thread.  grid = (NQB, ceil(H*D / (256 * columns per thread))); X is [T][H*D]; out is [NQB][H*D] float.
 template <bool F32>
 __global__ __launch_bounds__(256) void pool_kernel(const void* __restrict__ X, int cols, const int32_t* __restrict__ cu,
                                                    const int32_t* __restrict__ qb_off, const int32_t* __restrict__ qb_seq,
                                                    int B, float* __restrict__ out) {
+  constexpr int CPT = F32 ? 4 : 8;  // columns per thread
   const int qb = blockIdx.x;
-  const int c0 = (blockIdx.y * 256 + threadIdx.x) * 4;
+  const int c0 = (blockIdx.y * 256 + threadIdx.x) * CPT;
   if (c0 >= cols) return;
   const int s = qb_seq[qb];
   const int j = qb - qb_off[s];
   const int L = cu[s + 1] - cu[s];
   const int first = j * B, last = min((j + 1) * B, L);
   const int64_t row0 = (int64_t)cu[s] + first;
-  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  float a[CPT];
+#pragma unroll
+  for (int e = 0; e < CPT; ++e) a[e] = 0.f;
   if (F32) {
     const float* p = (const float*)X + row0 * cols + c0;
 #pragma unroll 8
     for (int r = 0; r < last - first; ++r) {
       float4 v = *(const float4*)(p + (int64_t)r * cols);
-      a0 += v.x; a1 += v.y; a2 += v.z; a3 += v.w;
+      a[0] += v.x; a[1] += v.y; a[2] += v.z; a[3] += v.w;
     }
   } else {
     const uint16_t* p = (const uint16_t*)X + row0 * cols + c0;
 #pragma unroll 8
     for (int r = 0; r < last - first; ++r) {
-      uint2 v = *(const uint2*)(p + (int64_t)r * cols);
-      a0 += bf16_bits_to_float(v.x & 0xffffu); a1 += bf16_bits_to_float(v.x >> 16);
-      a2 += bf16_bits_to_float(v.y & 0xffffu); a3 += bf16_bits_to_float(v.y >> 16);
+      const uint4 v = *(const uint4*)(p + (int64_t)r * cols);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        a[2 * e] += bf16_bits_to_float(w[e] & 0xffffu);
+        a[2 * e + 1] += bf16_bits_to_float(w[e] >> 16);
+      }
     }
   }
   const float inv = 1.0f / (float)(last - first);
-  *(float4*)(out + (int64_t)qb * cols + c0) = make_float4(a0 * inv, a1 * inv, a2 * inv, a3 * inv);
+  float* o = out + (int64_t)qb * cols + c0;
+#pragma unroll
+  for (int e = 0; e < CPT; e += 4) *(float4*)(o + e) = make_float4(a[e] * inv, a[e + 1] * inv, a[e + 2] * inv, a[e + 3] * inv);
 }
 
 // Score tiles on the fp32 matrix cores (the selection is taken on fp32 scores, so the operands stay
@@ -170,7 +179,8 @@ int launch_pool(const Geo& g, const sb_problem* p, const Tables& t, const void* 
   float* qbar = (float*)b;
   float* kbar = (float*)(b + align_up(sizeof(float) * (size_t)g.NQB * g.Hq * g.D));
   const int qcols = g.Hq * g.D, kcols = g.Hkv * g.D;
-  dim3 gq((unsigned)g.NQB, (unsigned)((qcols + 1023) / 1024)), gk((unsigned)g.NQB, (unsigned)((kcols + 1023) / 1024));
+  const int per_wg = 256 * (g.dtype == SB_F32 ? 4 : 8);  // columns per workgroup (head_dim is a multiple of 8)
+  dim3 gq((unsigned)g.NQB, (unsigned)((qcols + per_wg - 1) / per_wg)), gk((unsigned)g.NQB, (unsigned)((kcols + per_wg - 1) / per_wg));
   {
     KernelTimer kt(K_POOL, st);
     if (g.dtype == SB_F32) {
