@@ -122,6 +122,21 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ qb
   const float ninf = -__builtin_inff();
   float a[D / 4];  // this lane's quarter of query row 16 * wave + l16 (filled once the tile is staged)
   bool have_a = false;
+  // A key tile is fetched into registers one tile ahead (its loads are in flight while the tile before it is being
+  // multiplied) and written to LDS between the two barriers.
+  constexpr int PF = 64 * (D / 4) / 256;  // float4 per thread and key tile
+  float4 pf[PF];
+  auto fetch = [&](int jt) __attribute__((always_inline)) {
+    const int j0 = jt * 64, colsv = min(64, n - j0);
+#pragma unroll
+    for (int x = 0; x < PF; ++x) {
+      const int u = tid + 256 * x, r = u / (D / 4), cc = (u % (D / 4)) * 4;
+      pf[x] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (r < colsv) pf[x] = *(const float4*)(kbar + ((qb0 + j0 + r) * Hkv + g) * D + cc);
+    }
+  };
+  auto computed = [&](int jt) { return jt * 64 < n && jt <= it; };  // key tiles that are multiplied (a prefix of the chunk)
+  if (computed(jc * kScChunk)) fetch(jc * kScChunk);
   for (int c = 0; c < kScChunk; ++c) {
     const int jt = jc * kScChunk + c, j0 = jt * 64;
     if (j0 >= n) break;
@@ -137,13 +152,12 @@ __global__ __launch_bounds__(256) void score_kernel(const float* __restrict__ qb
       load_quarter<D>(a, qs + (16 * wave + l16) * LD, kq);
       have_a = true;
     }
-    const int colsv = min(64, n - j0);
-    for (int u = tid; u < 64 * (D / 4); u += 256) {
-      const int r = u / (D / 4), cc = (u % (D / 4)) * 4;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (r < colsv) v = *(const float4*)(kbar + ((qb0 + j0 + r) * Hkv + g) * D + cc);
-      *(float4*)(ks + r * LD + cc) = v;
+#pragma unroll
+    for (int x = 0; x < PF; ++x) {
+      const int u = tid + 256 * x, r = u / (D / 4), cc = (u % (D / 4)) * 4;
+      *(float4*)(ks + r * LD + cc) = pf[x];
     }
+    if (c + 1 < kScChunk && computed(jt + 1)) fetch(jt + 1);
     __syncthreads();
 #pragma unroll
     for (int c4 = 0; c4 < 4; ++c4) {
