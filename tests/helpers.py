@@ -56,13 +56,26 @@ class Run:
             self.rowptr = torch.from_numpy(np.ascontiguousarray(sel_override[0], dtype=np.int32)).to(DEV)
             self.idx = torch.from_numpy(np.ascontiguousarray(sel_override[1], dtype=np.int32)).to(DEV)
         self.plan = sb.sb_plan_worklist(self.pb, self.rowptr, self.idx)
-        self.o, self.lse = sb.sb_sparse_attn_fwd(self.pb, self.q, self.k, self.v, self.rowptr, self.idx, self.plan)
+        # every output starts as NaN: an element that no workgroup wrote stays NaN and fails all_written()
+        nan = lambda like, shape=None: torch.full(shape or like.shape, float("nan"), dtype=like.dtype, device=DEV)
+        self.o, self.lse = sb.sb_sparse_attn_fwd(self.pb, self.q, self.k, self.v, self.rowptr, self.idx, self.plan, o=nan(self.q),
+                                                 lse=torch.full((w.Hq, w.T), float("nan"), dtype=torch.float32, device=DEV))
         if do_bwd:
             self.dq, self.dk, self.dv = sb.sb_sparse_attn_bwd(self.pb, self.q, self.k, self.v, self.o, self.lse, self.do,
-                                                              self.rowptr, self.idx, self.plan)
+                                                              self.rowptr, self.idx, self.plan, dq=nan(self.q), dk=nan(self.k),
+                                                              dv=nan(self.k))
         torch.cuda.synchronize()
+        self.all_written(do_bwd)
         self.rowptr_h = self.rowptr.cpu().numpy()
         self.idx_h = self.idx.cpu().numpy()[: int(self.rowptr_h[-1])]
+
+    def all_written(self, bwd=True):
+        """Every element of every output has been written with a number (holds at any size; the sampled comparisons of the
+        full-size tests would not notice a work item that no workgroup took)."""
+        names = ("o", "lse") + (("dq", "dk", "dv") if bwd else ())
+        for n in names:
+            t = getattr(self, n)
+            assert bool(torch.isfinite(t).all()), f"{n}: elements left unwritten or not finite"
 
     def oracle_inputs(self):
         """What the checker sees: the storage values; float inputs are rounded to bf16 as the kernels do."""
