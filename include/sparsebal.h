@@ -33,7 +33,7 @@
  *     reports for the same problem; an undersized buffer is overrun, not detected.
  *   - A `ws` buffer is scratch of one call at a time (tables, counters, converted operands): calls that may overlap in
  *     time (different streams) need buffers of their own; calls ordered on one stream may share one.  The library keeps
- *     no device state between calls besides what `plan` and `ws` hold.
+ *     no device state between calls besides what `plan` and `ws` hold (and the built-in scratch of sb_select_topk_static).
  *   - Supported: block_size 64, 128 or 256; head_dim 64 or 128; Hq % Hkv == 0; n_s <= SB_MAX_BLOCKS_PER_SEQ;
  *     in SB_SELECT_PER_KVGROUP Hq/Hkv <= 8; selection entries and rows (at the granularity of 64-token tiles) must
  *     fit 32-bit row pointers.  Anything else returns SB_ERR_UNSUPPORTED.
