@@ -218,16 +218,18 @@ def test_caller_supplied_selection_and_determinism(mode, Hq, D):
         assert torch.equal(a, b)                       # run-to-run bitwise identical
 
 
-@pytest.mark.parametrize("mode", [0, 1])
-def test_attention_sink_selection_splits_heavy_columns(mode):
+@pytest.mark.parametrize("mode,B,D", [(0, 64, 64), (1, 64, 64), (0, 128, 128)])
+def test_attention_sink_selection_splits_heavy_columns(mode, B, D):
     """A caller-supplied selection in which every query block keeps block 0 plus the blocks right before it (the shape
     real attention maps have): block 0 of the long sequence is kept by 701 query blocks of four heads, more than the
     split weight, so its column is cut into parts whose fp32 partial dK/dV are reduced in a fixed order."""
-    w = synth.Workload("sink", [64 * 700 + 9, 300, 64 * 40], 8, 2, 64, topk=[4, 3, 5], seed=71)
+    nlong = 700 if B == 64 else 300   # (with 128-token blocks the plan works on two 64-token tiles per block: both tile columns of block 0 are split)
+    w = synth.Workload("sink", [B * nlong + 9, 300, B * 40], 8, 2, D, B=B, topk=[4, 3, 5], seed=71)
     Hs = 8 if mode == 0 else 2
-    sel = synth.sink_selection(w.cu, 64, w.topk, Hs)
+    sel = synth.sink_selection(w.cu, B, w.topk, Hs)
     r1 = Run(w, mode, sel_override=sel)
-    check_plan(r1)
+    if B == 64:
+        check_plan(r1)
     pv = sb.plan_views(r1.pb, r1.plan)
     assert len(pv["split_cols"]) >= 2 and pv["slots_used"] >= 6, (pv["split_cols"], pv["slots_used"])
     # dK/dV of a split column add up the bf16-rounded P and dS of ~180 000 query rows (2^-9 relative each): a random walk
@@ -240,12 +242,13 @@ def test_attention_sink_selection_splits_heavy_columns(mode):
     dQ, dK, dV = orc.attn_bwd(r1.opb, q, k, v, do, r1.rowptr_h, r1.idx_h, r1.scale)
     stats = {"O": check_close("O", to_host_f32(r1.o), O), "LSE": check_lse(r1.lse.cpu().numpy(), LSE),
              "dQ": check_close("dQ", to_host_f32(r1.dq), dQ)}
-    NQB = r1.pb.layout.num_qblocks
+    NQB = len(pv["qb_seq"])                                   # columns are 64-token tiles
+    tile_off = np.asarray(pv["qb_off"], dtype=np.int64)
     heavy = np.zeros((w.T, w.Hkv), dtype=bool)
     for col, _, _ in pv["split_cols"]:
         g, qb = divmod(int(col), NQB)
-        s = int(np.searchsorted(r1.opb.qb_off, qb, side="right") - 1)
-        a = int(w.cu[s]) + 64 * (qb - int(r1.opb.qb_off[s]))
+        s = int(np.searchsorted(tile_off, qb, side="right") - 1)
+        a = int(w.cu[s]) + 64 * (qb - int(tile_off[s]))
         b = min(a + 64, int(w.cu[s + 1]))
         heavy[a:b, g] = True
         for name, got, ref in (("dK", r1.dk, dK), ("dV", r1.dv, dV)):
